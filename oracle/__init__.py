@@ -1,0 +1,244 @@
+"""ctypes front end of the CPU oracle (baoc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's cpu_baseline leg.  Nothing here touches the HIP library and the
+HIP library never touches this.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "baoc_oracle.c")
+_LIB = os.path.join(_HERE, "libbaoc_oracle.so")
+
+# -ffp-contract=off: every fp32 operation of the state update is rounded once, as written
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force=False):
+    """Compile the oracle with gcc (seconds). Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.run(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"], check=True)
+    return _LIB
+
+
+class Stats(C.Structure):
+    _fields_ = [("numel", C.c_uint64), ("steps", C.c_uint32), ("n_cos", C.c_uint32)] + [
+        (n, C.c_double) for n in (
+            "rho_bar", "cos_last", "snr", "A", "q10", "q90",
+            "Q16", "Q8", "lQ32", "lQ16", "lQ8",
+            "err_m16", "err_v16", "err_m8", "err_v8",
+            "s_A", "s_rho", "s_snr", "s_M", "C_tilde", "s_F",
+            "m_sq", "v_l1", "g_sq_last")]
+
+    def asdict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+STAT_FIELDS = [n for n, _ in Stats._fields_]
+
+
+class RiskParams(C.Structure):
+    _fields_ = [(n, C.c_double) for n in (
+        "gamma", "A_low", "A_high", "rho_low", "rho_high", "eta_low", "eta_high")] + [
+        ("use_snr_gate", C.c_int), ("lambda_pref", C.c_double)]
+
+
+def default_risk_params(**kw):
+    """gamma of Eq. 1 and the anchors of App. A."""
+    import math
+    p = RiskParams(0.1, math.log(2.0), math.log(10.0), 0.2, 0.6, 0.0, 2.0, 1, 0.0)
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, u64, u32, f32, f64, i64 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_float, C.c_double, C.c_int64
+        L.orc_block_new.restype = vp
+        L.orc_block_new.argtypes = [u64, f32, f32, f64, f64, f32, u32]
+        L.orc_block_free.argtypes = [vp]
+        for n in ("orc_block_m", "orc_block_v", "orc_block_p"):
+            getattr(L, n).restype = C.POINTER(C.c_float)
+            getattr(L, n).argtypes = [vp]
+        L.orc_block_step_f32.argtypes = [vp, vp]
+        L.orc_block_step_bf16.argtypes = [vp, vp]
+        L.orc_block_finalize.argtypes = [vp, C.POINTER(RiskParams), f64, f64, C.POINTER(Stats)]
+        L.orc_bf16_round.restype = f32
+        L.orc_bf16_round.argtypes = [f32]
+        L.orc_q8_code.restype = f32
+        L.orc_q8_code.argtypes = [f32, f32, f32]
+        L.orc_quantile.restype = f64
+        L.orc_quantile.argtypes = [vp, u64, f64]
+        L.orc_agg.restype = f64
+        L.orc_agg.argtypes = [C.c_int] * 5
+        L.orc_phi.restype = f64
+        L.orc_phi.argtypes = [C.POINTER(Stats), C.c_char_p, C.c_int, C.POINTER(RiskParams)]
+        for n in ("orc_allocate_brute", "orc_allocate_dp", "orc_allocate_bnb"):
+            if hasattr(L, n):
+                getattr(L, n).argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp,
+                                          C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
+        L.orc_integerise.argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp, vp, vp, C.POINTER(i64)]
+        _lib = L
+    return _lib
+
+
+ORC_OK, ORC_INVALID, ORC_INFEASIBLE, ORC_TOO_BIG = 0, -1, -5, -6
+
+
+class Block:
+    """Profiler state of one parameter block; step() takes that block's slice."""
+
+    def __init__(self, numel, beta_m=0.9, beta_v=0.999, beta_rho=0.9, eps=1e-12, eps_u=1e-8, qb=256):
+        self.numel = int(numel)
+        self._h = lib().orc_block_new(self.numel, beta_m, beta_v, beta_rho, eps, eps_u, qb)
+        if not self._h:
+            raise MemoryError("oracle block")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().orc_block_free(self._h)
+            self._h = None
+
+    def step(self, g):
+        """g: float32 array, or uint16 array holding bf16 bit patterns."""
+        g = np.ascontiguousarray(g)
+        assert g.size == self.numel
+        if g.dtype == np.float32:
+            rc = lib().orc_block_step_f32(self._h, g.ctypes.data)
+        elif g.dtype == np.uint16:
+            rc = lib().orc_block_step_bf16(self._h, g.ctypes.data)
+        else:
+            raise TypeError("gradient dtype must be float32 or uint16 (bf16 bits)")
+        if rc:
+            raise MemoryError("oracle step")
+
+    def _arr(self, fn):
+        p = fn(self._h)
+        return np.ctypeslib.as_array(p, shape=(self.numel,)).copy()
+
+    @property
+    def m(self):
+        return self._arr(lib().orc_block_m)
+
+    @property
+    def v(self):
+        return self._arr(lib().orc_block_v)
+
+    @property
+    def p(self):
+        return self._arr(lib().orc_block_p)
+
+    def finalize(self, rp=None, C_raw=0.0, F_raw=0.0):
+        rp = rp or default_risk_params()
+        st = Stats()
+        if lib().orc_block_finalize(self._h, C.byref(rp), C_raw, F_raw, C.byref(st)):
+            raise MemoryError("oracle finalize")
+        return st
+
+
+class Profiler:
+    """All blocks of a layout over one flat gradient buffer.
+
+    blocks: sequence of (offset, numel) in elements of the flat buffer.
+    """
+
+    def __init__(self, blocks, **params):
+        self.blocks = [(int(o), int(n)) for o, n in blocks]
+        self.state = [Block(n, **params) for _, n in self.blocks]
+
+    def step(self, flat, only=None):
+        idx = range(len(self.blocks)) if only is None else only
+        for i in idx:
+            o, n = self.blocks[i]
+            self.state[i].step(flat[o:o + n])
+
+    def finalize(self, configs, rp=None, pref_mask=None, C_raw=None, F_raw=None, only=None):
+        """-> (list of Stats, risk table Phi[N,K] as float64)."""
+        rp = rp or default_risk_params()
+        idx = list(range(len(self.blocks)) if only is None else only)
+        stats, rows = [], []
+        for i in idx:
+            st = self.state[i].finalize(rp, 0.0 if C_raw is None else float(C_raw[i]),
+                                        0.0 if F_raw is None else float(F_raw[i]))
+            stats.append(st)
+            rows.append([phi(st, c, bool(pref_mask[k]) if pref_mask is not None else False, rp)
+                         for k, c in enumerate(configs)])
+        return stats, np.array(rows, dtype=np.float64).reshape(len(idx), len(configs))
+
+
+def phi(stats, cfg, preferred=False, rp=None):
+    rp = rp or default_risk_params()
+    return lib().orc_phi(C.byref(stats), bytes(bytearray(int(x) for x in cfg)), int(preferred), C.byref(rp))
+
+
+def agg(cfg):
+    return lib().orc_agg(*[int(x) for x in cfg])
+
+
+def bf16_round(x):
+    return lib().orc_bf16_round(float(x))
+
+
+def q8_code(x, a, L):
+    return lib().orc_q8_code(float(x), float(a), float(L))
+
+
+def quantile(x, q):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return lib().orc_quantile(x.ctypes.data, x.size, q)
+
+
+def _allocate(fn, risk, mem, time, mem_budget, time_budget_sum, forbidden):
+    risk = np.ascontiguousarray(risk, dtype=np.float64)
+    N, K = risk.shape
+    mem = np.ascontiguousarray(mem, dtype=np.int64).reshape(N, K)
+    time = np.ascontiguousarray(time, dtype=np.float64).reshape(N, K)
+    fb = None if forbidden is None else np.ascontiguousarray(forbidden, dtype=np.uint8).reshape(N, K)
+    choice = np.zeros(N, dtype=np.uint32)
+    obj, om, ot = C.c_double(), C.c_int64(), C.c_double()
+    rc = fn(risk.ctypes.data, mem.ctypes.data, time.ctypes.data, N, K, int(mem_budget),
+            float(time_budget_sum), None if fb is None else fb.ctypes.data, choice.ctypes.data,
+            C.byref(obj), C.byref(om), C.byref(ot))
+    return rc, choice, obj.value, om.value, ot.value
+
+
+def allocate_brute(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
+    """Exhaustive K^N enumeration -> (rc, choice, objective, mem, time)."""
+    return _allocate(lib().orc_allocate_brute, risk, mem, time, mem_budget, time_budget_sum, forbidden)
+
+
+def allocate_dp(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
+    """Textbook two-row knapsack dynamic programme (small integer resources)."""
+    return _allocate(lib().orc_allocate_dp, risk, mem, time, mem_budget, time_budget_sum, forbidden)
+
+
+def allocate_bnb(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
+    """Depth-first branch and bound, for instances the other two cannot reach."""
+    return _allocate(lib().orc_allocate_bnb, risk, mem, time, mem_budget, time_budget_sum, forbidden)
+
+
+def integerise(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
+    risk = np.ascontiguousarray(risk, dtype=np.float64)
+    N, K = risk.shape
+    mem = np.ascontiguousarray(mem, dtype=np.int64).reshape(N, K)
+    time = np.ascontiguousarray(time, dtype=np.float64).reshape(N, K)
+    fb = None if forbidden is None else np.ascontiguousarray(forbidden, dtype=np.uint8).reshape(N, K)
+    phi_i = np.zeros((N, K), np.int64)
+    tau = np.zeros((N, K), np.int64)
+    ok = np.zeros((N, K), np.uint8)
+    bt = C.c_int64()
+    rc = lib().orc_integerise(risk.ctypes.data, mem.ctypes.data, time.ctypes.data, N, K, int(mem_budget),
+                              float(time_budget_sum), None if fb is None else fb.ctypes.data,
+                              phi_i.ctypes.data, tau.ctypes.data, ok.ctypes.data, C.byref(bt))
+    return rc, phi_i, tau, ok, bt.value

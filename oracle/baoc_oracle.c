@@ -1,0 +1,519 @@
+/*
+ * CPU oracle for the BAOC gradient-stream profiler, risk table and allocation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, sequential, obviously
+ * correct statement of what the method computes.  It shares no code with the
+ * HIP library; only tests, the smoke check and the benchmark's cpu_baseline
+ * leg may call it.  The product path never does.
+ *
+ * Precision.  The per-coordinate EMA states m, v are 32-bit floats (the
+ * "32-bit" state of Eq. 8 / the fp32 Adam state of the StateMem definition)
+ * and are advanced with one fixed sequence of fp32 operations, so that every
+ * decision a quantiser takes (a bf16 rounding, an 8-bit code) is a function
+ * of bit-identical inputs on both sides.  Everything that is derived from the
+ * states (sums, update directions, cosines, errors, quantiles, risk) is
+ * evaluated in fp64.  Build with -ffp-contract=off and without -ffast-math
+ * so that each fp32 operation below is rounded exactly once, as written.
+ *
+ * Pins (tests/test_oracle_*.py): closed forms of the EMA, cosine special
+ * cases, exactly representable values under both quantisers, error bounds of
+ * the quantisers, quantiles against a sort-based library routine, chi-square
+ * anisotropy of isotropic noise, the normalisation constants of App. A,
+ * Agg(c) of Eq. 1, and exhaustive enumeration / dynamic programming for the
+ * allocation.  The end-to-end trajectory on a workload is parity unpinned
+ * against the paper: it prints no statistic, risk or allocation.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* Profiler state of one parameter block B_i (Sec. 3.1, Sec. 3.3)      */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    uint64_t d;          /* d_i, coordinates in the block (Omega_i = all)   */
+    uint32_t t;          /* sampled steps seen                              */
+    uint32_t n_cos;      /* cosines folded into rho_bar                     */
+    uint32_t qb;         /* coordinates per 8-bit quantisation group        */
+    float beta_m, beta_v;
+    double beta_rho, eps;
+    float eps_u;
+    float *m, *v, *p;    /* m-hat, v-hat, previous gradient g_{t-1}         */
+    double rho_bar, cos_last;
+    double S_gg, S_pp, S_gp;      /* |g_t|^2, |g_{t-1}|^2, <g_t, g_{t-1}>   */
+    double S_mm, S_v1, S_vv;      /* |m|^2, |v|_1, |v|^2                     */
+    double U0;                    /* |u32|^2                                */
+    double U1[2], U2[2];          /* <u32,u^b>, |u^b|^2 ; index 0: b=16, 1: b=8 */
+    double Em[2], Ev[2];          /* |m^b - m|^2, |v^b - v|^2               */
+} orc_block;
+
+orc_block *orc_block_new(uint64_t d, float beta_m, float beta_v, double beta_rho,
+                         double eps, float eps_u, uint32_t qb)
+{
+    orc_block *b = (orc_block *)calloc(1, sizeof(orc_block));
+    if (!b) return NULL;
+    b->d = d; b->qb = qb;
+    b->beta_m = beta_m; b->beta_v = beta_v; b->beta_rho = beta_rho;
+    b->eps = eps; b->eps_u = eps_u;
+    b->m = (float *)calloc(d ? d : 1, sizeof(float));
+    b->v = (float *)calloc(d ? d : 1, sizeof(float));
+    b->p = (float *)calloc(d ? d : 1, sizeof(float));
+    if (!b->m || !b->v || !b->p) { free(b->m); free(b->v); free(b->p); free(b); return NULL; }
+    return b;
+}
+
+void orc_block_free(orc_block *b)
+{
+    if (!b) return;
+    free(b->m); free(b->v); free(b->p); free(b);
+}
+
+const float *orc_block_m(const orc_block *b) { return b->m; }
+const float *orc_block_v(const orc_block *b) { return b->v; }
+const float *orc_block_p(const orc_block *b) { return b->p; }
+
+/* bf16 storage: the upper 16 bits of an IEEE binary32. Widening is exact. */
+static float bf16_widen(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16; float f; memcpy(&f, &u, 4); return f;
+}
+
+/* Round-to-nearest-even of a binary32 to the bf16 grid, returned as binary32. */
+static float bf16_round(float x)
+{
+    uint32_t u; memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {        /* NaN stays NaN */
+        u |= 0x00400000u; u &= 0xffff0000u;
+    } else {
+        u += 0x7fffu + ((u >> 16) & 1u);
+        u &= 0xffff0000u;
+    }
+    float r; memcpy(&r, &u, 4); return r;
+}
+
+float orc_bf16_round(float x) { return bf16_round(x); }
+
+/*
+ * Block-wise absmax linear 8-bit quantiser (the reading of the "standard
+ * quantizer" of Eq. 8 for b = 8).  a = the group's absmax, L = 127 for the
+ * signed first moment, 255 for the non-negative second moment.  The integer
+ * code is decided in fp32:  k = rint_fp32( x (*) (L (/) a) ), ties to even,
+ * with (*) and (/) the correctly rounded binary32 operations; when L/a is not
+ * finite (a == 0, or so small that the scale overflows) every code is 0.
+ * The de-quantised value a*k/L is formed in fp64.
+ */
+static double q8_dequant(float x, float a, float L)
+{
+    float s = L / a;
+    if (!(s < INFINITY)) return 0.0;
+    float k = rintf(x * s);
+    return (double)a * (double)k / (double)L;
+}
+
+float orc_q8_code(float x, float a, float L)
+{
+    float s = L / a;
+    if (!(s < INFINITY)) return 0.0f;
+    return rintf(x * s);
+}
+
+/* One sampled step for one block; g widened exactly to binary32 beforehand. */
+static void block_step(orc_block *b, const float *g)
+{
+    const uint64_t d = b->d;
+    const float bm = b->beta_m, bv = b->beta_v;
+    const float om_m = 1.0f - bm, om_v = 1.0f - bv;      /* 1 - beta, in fp32 */
+    b->t += 1;
+
+    /* Eq. 3: m <- beta_m m + (1-beta_m) g ; v <- beta_v v + (1-beta_v) g*g.
+       fp32: the new term is rounded, then one fused multiply-add. */
+    for (uint64_t j = 0; j < d; ++j) {
+        float tm = om_m * g[j];
+        float tv = (om_v * g[j]) * g[j];
+        b->m[j] = fmaf(bm, b->m[j], tm);
+        b->v[j] = fmaf(bv, b->v[j], tv);
+    }
+
+    /* Eq. 5 (left): cosine of consecutive gradients, EMA with beta_rho.
+       The first step has no predecessor and leaves rho_bar untouched; the
+       first cosine initialises it. NaN cosines count as 0 (App. A.1). */
+    double S_gg = 0.0, S_gp = 0.0;
+    for (uint64_t j = 0; j < d; ++j) {
+        S_gg += (double)g[j] * (double)g[j];
+        S_gp += (double)g[j] * (double)b->p[j];
+    }
+    b->S_gg = S_gg; b->S_gp = (b->t >= 2) ? S_gp : 0.0;
+    if (b->t >= 2) {
+        double c = S_gp / (sqrt(S_gg) * sqrt(b->S_pp) + b->eps);
+        if (isnan(c)) c = 0.0;
+        b->cos_last = c;
+        if (b->n_cos == 0) b->rho_bar = c;
+        else b->rho_bar = b->beta_rho * b->rho_bar + (1.0 - b->beta_rho) * c;
+        b->n_cos += 1;
+    }
+    memcpy(b->p, g, d * sizeof(float));
+    b->S_pp = S_gg;
+
+    /* Eq. 5 (right): the sums behind rho_snr = |m|^2 / (|v|_1 + eps). */
+    double S_mm = 0.0, S_v1 = 0.0, S_vv = 0.0;
+    for (uint64_t j = 0; j < d; ++j) {
+        double m = b->m[j], v = b->v[j];
+        S_mm += m * m; S_v1 += v; S_vv += v * v;
+    }
+    b->S_mm = S_mm; b->S_v1 = S_v1; b->S_vv = S_vv;
+
+    /* Eq. 8: update direction u = m / (sqrt(v) + eps_u) from the 32-bit state
+       and from the state after a one-shot quantise/de-quantise to b bits. */
+    double U0 = 0.0, U1[2] = {0, 0}, U2[2] = {0, 0}, Em[2] = {0, 0}, Ev[2] = {0, 0};
+    const double eu = (double)b->eps_u;
+    for (uint64_t s = 0; s < d; s += b->qb) {
+        uint64_t e = s + b->qb < d ? s + b->qb : d;
+        float a_m = 0.0f, a_v = 0.0f;              /* group absmax (NaN ignored) */
+        for (uint64_t j = s; j < e; ++j) {
+            a_m = fmaxf(a_m, fabsf(b->m[j]));
+            a_v = fmaxf(a_v, b->v[j]);
+        }
+        for (uint64_t j = s; j < e; ++j) {
+            double m = b->m[j], v = b->v[j];
+            double u32 = m / (sqrt(v) + eu);
+            double mq[2], vq[2];
+            mq[0] = bf16_round(b->m[j]);          vq[0] = bf16_round(b->v[j]);
+            mq[1] = q8_dequant(b->m[j], a_m, 127.0f);
+            vq[1] = q8_dequant(b->v[j], a_v, 255.0f);
+            U0 += u32 * u32;
+            for (int k = 0; k < 2; ++k) {
+                double ub = mq[k] / (sqrt(vq[k]) + eu);
+                U1[k] += u32 * ub;
+                U2[k] += ub * ub;
+                Em[k] += (mq[k] - m) * (mq[k] - m);
+                Ev[k] += (vq[k] - v) * (vq[k] - v);
+            }
+        }
+    }
+    b->U0 = U0;
+    for (int k = 0; k < 2; ++k) { b->U1[k] = U1[k]; b->U2[k] = U2[k]; b->Em[k] = Em[k]; b->Ev[k] = Ev[k]; }
+}
+
+int orc_block_step_f32(orc_block *b, const float *g) { block_step(b, g); return 0; }
+
+int orc_block_step_bf16(orc_block *b, const uint16_t *g)
+{
+    float *w = (float *)malloc((b->d ? b->d : 1) * sizeof(float));
+    if (!w) return -1;
+    for (uint64_t j = 0; j < b->d; ++j) w[j] = bf16_widen(g[j]);
+    block_step(b, w);
+    free(w);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Finalize: raw metrics, normalisation (App. A) and risk (Eq. 11)     */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    uint64_t numel; uint32_t steps; uint32_t n_cos;
+    double rho_bar, cos_last, snr, A, q10, q90;
+    double Q16, Q8, lQ32, lQ16, lQ8;
+    double err_m16, err_v16, err_m8, err_v8;
+    double s_A, s_rho, s_snr, s_M, C_tilde, s_F;
+    double m_sq, v_l1, g_sq_last;
+} orc_stats;
+
+typedef struct {
+    double gamma, A_low, A_high, rho_low, rho_high, eta_low, eta_high;
+    int use_snr_gate;
+    double lambda_pref;
+} orc_risk_params;
+
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* q-th quantile: linear interpolation between the order statistics that
+   bracket position q (d-1) of the ascending sort. */
+static double quantile_sorted(const double *s, uint64_t d, double q)
+{
+    double pos = q * (double)(d - 1);
+    uint64_t lo = (uint64_t)floor(pos);
+    uint64_t hi = lo + 1 < d ? lo + 1 : d - 1;
+    return s[lo] + (pos - (double)lo) * (s[hi] - s[lo]);
+}
+
+double orc_quantile(const float *x, uint64_t d, double q)
+{
+    double *s = (double *)malloc(d * sizeof(double));
+    for (uint64_t j = 0; j < d; ++j) s[j] = x[j];
+    qsort(s, d, sizeof(double), cmp_double);
+    double r = quantile_sorted(s, d, q);
+    free(s);
+    return r;
+}
+
+static double clip(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/* Eq. 8 then Eq. 12 (clip to [eps,1], NaN -> 0 first) */
+static double cosine_Q(double U1, double U0, double U2, double eps)
+{
+    double q = U1 / (sqrt(U0) * sqrt(U2) + eps);
+    if (isnan(q)) q = 0.0;
+    return clip(q, eps, 1.0);
+}
+
+int orc_block_finalize(const orc_block *b, const orc_risk_params *rp, double C_raw, double F_raw,
+                       orc_stats *o)
+{
+    const double eps = b->eps;
+    memset(o, 0, sizeof(*o));
+    o->numel = b->d; o->steps = b->t; o->n_cos = b->n_cos;
+    o->rho_bar = b->n_cos ? b->rho_bar : 0.0;
+    o->cos_last = b->cos_last;
+    o->m_sq = b->S_mm; o->v_l1 = b->S_v1; o->g_sq_last = b->S_gg;
+
+    /* Eq. 5 right */
+    o->snr = b->S_mm / (b->S_v1 + eps);
+
+    /* Eq. 4: quantile ratio of v-hat */
+    {
+        double *s = (double *)malloc(b->d * sizeof(double));
+        if (!s) return -1;
+        for (uint64_t j = 0; j < b->d; ++j) s[j] = b->v[j];
+        qsort(s, b->d, sizeof(double), cmp_double);
+        o->q10 = quantile_sorted(s, b->d, 0.1);
+        o->q90 = quantile_sorted(s, b->d, 0.9);
+        free(s);
+        o->A = log((o->q90 + eps) / (o->q10 + eps));
+    }
+
+    /* Eq. 8, Eq. 12, Eq. 21 */
+    double Q32 = cosine_Q(b->U0, b->U0, b->U0, eps);
+    o->Q16 = cosine_Q(b->U1[0], b->U0, b->U2[0], eps);
+    o->Q8  = cosine_Q(b->U1[1], b->U0, b->U2[1], eps);
+    o->lQ32 = -log(Q32 + eps);
+    o->lQ16 = -log(o->Q16 + eps);
+    o->lQ8  = -log(o->Q8 + eps);
+
+    /* relative L2 error of the states themselves in the cheaper precisions */
+    o->err_m16 = sqrt(b->Em[0]) / (sqrt(b->S_mm) + eps);
+    o->err_m8  = sqrt(b->Em[1]) / (sqrt(b->S_mm) + eps);
+    o->err_v16 = sqrt(b->Ev[0]) / (sqrt(b->S_vv) + eps);
+    o->err_v8  = sqrt(b->Ev[1]) / (sqrt(b->S_vv) + eps);
+
+    /* App. A: Eq. 14 (s_A), Eq. 16 (s_rho), Eq. 18 (s_snr), Eq. 19 (s_M),
+       Eq. 20 (C-tilde), Eq. 21' (s_F) */
+    o->s_A   = clip((o->A - rp->A_low) / (rp->A_high - rp->A_low), 0.0, 1.0);
+    o->s_rho = clip((o->rho_bar - rp->rho_low) / (rp->rho_high - rp->rho_low), 0.0, 1.0);
+    o->s_snr = clip((log(1.0 + o->snr) - rp->eta_low) / (rp->eta_high - rp->eta_low), 0.0, 1.0);
+    o->s_M   = rp->use_snr_gate ? o->s_rho * o->s_snr : o->s_rho;
+    o->C_tilde = log(1.0 + C_raw);
+    o->s_F   = clip(F_raw, 0.0, 1.0);
+    return 0;
+}
+
+/* Eq. 1: Agg(c) = (1-y_a)+(1-y_m)+(1-y_d)+y_f+32/b-1 */
+double orc_agg(int y_a, int y_m, int y_d, int y_f, int bits)
+{
+    return (1 - y_a) + (1 - y_m) + (1 - y_d) + y_f + 32.0 / (double)bits - 1.0;
+}
+
+/* Eq. 11 with the soft preference of Sec. 3.2 and the regulariser of Eq. 1:
+   Phi = R - lambda_pref [c in C_pref] + gamma Agg(c). cfg = (y_a,y_m,y_d,y_f,bits). */
+double orc_phi(const orc_stats *z, const uint8_t cfg[5], int preferred, const orc_risk_params *rp)
+{
+    int y_a = cfg[0], y_m = cfg[1], y_d = cfg[2], y_f = cfg[3], bits = cfg[4];
+    double lQ = bits == 32 ? z->lQ32 : (bits == 16 ? z->lQ16 : z->lQ8);
+    double R = z->s_A * (1 - y_a) + z->s_M * (1 - y_m) + z->C_tilde * (1 - y_d) + z->s_F * y_f + lQ;
+    if (preferred) R -= rp->lambda_pref;
+    return R + rp->gamma * orc_agg(y_a, y_m, y_d, y_f, bits);
+}
+
+/* ------------------------------------------------------------------ */
+/* Allocation (Eq. 2): exact reference solvers                          */
+/* ------------------------------------------------------------------ */
+
+#define ORC_OK 0
+#define ORC_INFEASIBLE (-5)
+#define ORC_TOO_BIG (-6)
+#define ORC_INVALID (-1)
+
+#define PHI_SCALE 1e9
+#define PHI_CLAMP 1e6
+#define TAU_SCALE 1e6
+
+/* Integer instance: phi = llround(Phi 1e9) with |Phi| clamped to 1e6,
+   tau = llround(r 1e6); a pair is excluded when forbidden (hard constraint of
+   Sec. 3.2) or when its risk or time is not finite. */
+typedef struct {
+    uint32_t N, K;
+    int64_t *phi, *mem, *tau;
+    uint8_t *ok;
+    int64_t B_mem, B_tau;
+} int_instance;
+
+static int integerise(const double *risk, const int64_t *mem, const double *time,
+                      uint32_t N, uint32_t K, int64_t B_mem, double time_budget_sum,
+                      const uint8_t *forbidden, int_instance *I)
+{
+    size_t n = (size_t)N * K;
+    I->N = N; I->K = K;
+    I->phi = (int64_t *)malloc(n * 8); I->mem = (int64_t *)malloc(n * 8);
+    I->tau = (int64_t *)malloc(n * 8); I->ok = (uint8_t *)malloc(n);
+    I->B_mem = B_mem;
+    double tb = time_budget_sum;
+    if (isnan(tb)) return ORC_INVALID;
+    if (tb > 9e12) tb = 9e12;           /* "no limit": beyond any sum of clamped tau */
+    if (tb < -9e12) tb = -9e12;
+    I->B_tau = llround(tb * TAU_SCALE);
+    for (size_t k = 0; k < n; ++k) {
+        int ok = !(forbidden && forbidden[k]) && isfinite(risk[k]) && isfinite(time[k]);
+        if (mem[k] < 0) return ORC_INVALID;
+        I->ok[k] = (uint8_t)ok;
+        double r = ok ? clip(risk[k], -PHI_CLAMP, PHI_CLAMP) : 0.0;
+        double t = ok ? clip(time[k], -PHI_CLAMP, PHI_CLAMP) : 0.0;
+        I->phi[k] = llround(r * PHI_SCALE);
+        I->tau[k] = llround(t * TAU_SCALE);
+        I->mem[k] = mem[k];
+    }
+    return ORC_OK;
+}
+
+static void inst_free(int_instance *I) { free(I->phi); free(I->mem); free(I->tau); free(I->ok); }
+
+static void report(const int_instance *I, const uint32_t *x, double *obj, int64_t *omem, double *otime)
+{
+    int64_t z = 0, m = 0, t = 0;
+    for (uint32_t i = 0; i < I->N; ++i) {
+        size_t k = (size_t)i * I->K + x[i];
+        z += I->phi[k]; m += I->mem[k]; t += I->tau[k];
+    }
+    if (obj) *obj = (double)z / PHI_SCALE;
+    if (omem) *omem = m;
+    if (otime) *otime = (double)t / TAU_SCALE;
+}
+
+/* Exhaustive enumeration of all K^N assignments in lexicographic order
+   (block 1 most significant); a later assignment replaces the incumbent only
+   when strictly better, so ties resolve to the lexicographically smallest. */
+int orc_allocate_brute(const double *risk, const int64_t *mem, const double *time,
+                       uint32_t N, uint32_t K, int64_t B_mem, double time_budget_sum,
+                       const uint8_t *forbidden, uint32_t *out_choice,
+                       double *out_obj, int64_t *out_mem, double *out_time)
+{
+    if (pow((double)K, (double)N) > 2e8) return ORC_TOO_BIG;
+    int_instance I;
+    int rc = integerise(risk, mem, time, N, K, B_mem, time_budget_sum, forbidden, &I);
+    if (rc) { inst_free(&I); return rc; }
+    uint32_t *x = (uint32_t *)calloc(N, 4), *best = (uint32_t *)calloc(N, 4);
+    int found = 0; int64_t zbest = 0;
+    for (;;) {
+        int64_t z = 0, m = 0, t = 0; int ok = 1;
+        for (uint32_t i = 0; i < N; ++i) {
+            size_t k = (size_t)i * K + x[i];
+            if (!I.ok[k]) { ok = 0; break; }
+            z += I.phi[k]; m += I.mem[k]; t += I.tau[k];
+        }
+        if (ok && m <= I.B_mem && t <= I.B_tau && (!found || z < zbest)) {
+            found = 1; zbest = z; memcpy(best, x, N * 4);
+        }
+        int i = (int)N - 1;                       /* odometer, last block fastest */
+        while (i >= 0 && ++x[i] == K) { x[i] = 0; --i; }
+        if (i < 0) break;
+    }
+    if (found) { memcpy(out_choice, best, N * 4); report(&I, best, out_obj, out_mem, out_time); }
+    free(x); free(best); inst_free(&I);
+    return found ? ORC_OK : ORC_INFEASIBLE;
+}
+
+static int64_t gcd64(int64_t a, int64_t b) { while (b) { int64_t t = a % b; a = b; b = t; } return a < 0 ? -a : a; }
+
+/* Textbook multiple-choice-knapsack dynamic programme over the two resource
+   rows.  f_i(w,t) = least objective of blocks i..N-1 within remaining
+   capacities (w,t) (in units of the gcd of each row).  The forward
+   reconstruction takes, block by block, the smallest configuration index
+   that still reaches the optimum: the lexicographically smallest optimum. */
+int orc_allocate_dp(const double *risk, const int64_t *mem, const double *time,
+                    uint32_t N, uint32_t K, int64_t B_mem, double time_budget_sum,
+                    const uint8_t *forbidden, uint32_t *out_choice,
+                    double *out_obj, int64_t *out_mem, double *out_time)
+{
+    int_instance I;
+    int rc = integerise(risk, mem, time, N, K, B_mem, time_budget_sum, forbidden, &I);
+    if (rc) { inst_free(&I); return rc; }
+    size_t n = (size_t)N * K;
+    int64_t gm = 0, gt = 0, summ = 0, sumt = 0;
+    for (uint32_t i = 0; i < N; ++i) {
+        int64_t mm = 0, mt = 0;
+        for (uint32_t c = 0; c < K; ++c) {
+            size_t k = (size_t)i * K + c;
+            if (!I.ok[k]) continue;
+            if (I.tau[k] < 0) { inst_free(&I); return ORC_INVALID; }
+            gm = gcd64(gm, I.mem[k]); gt = gcd64(gt, I.tau[k]);
+            if (I.mem[k] > mm) mm = I.mem[k];
+            if (I.tau[k] > mt) mt = I.tau[k];
+        }
+        summ += mm; sumt += mt;
+    }
+    if (gm == 0) gm = 1;
+    if (gt == 0) gt = 1;
+    if (I.B_mem < 0 || I.B_tau < 0) { inst_free(&I); return ORC_INFEASIBLE; }
+    int64_t W = (I.B_mem < summ ? I.B_mem : summ) / gm;   /* capacities beyond the max sum are slack */
+    int64_t T = (I.B_tau < sumt ? I.B_tau : sumt) / gt;
+    if ((double)(W + 1) * (double)(T + 1) * (double)(N + 1) > 3e8) { inst_free(&I); return ORC_TOO_BIG; }
+    size_t plane = (size_t)(W + 1) * (size_t)(T + 1);
+    const int64_t INF = INT64_MAX / 4;
+    int64_t *f = (int64_t *)malloc((size_t)(N + 1) * plane * 8);
+    for (size_t s = 0; s < plane; ++s) f[(size_t)N * plane + s] = 0;
+    for (int i = (int)N - 1; i >= 0; --i)
+        for (int64_t w = 0; w <= W; ++w)
+            for (int64_t t = 0; t <= T; ++t) {
+                int64_t best = INF;
+                for (uint32_t c = 0; c < K; ++c) {
+                    size_t k = (size_t)i * K + c;
+                    if (!I.ok[k]) continue;
+                    int64_t dw = I.mem[k] / gm, dt = I.tau[k] / gt;
+                    if (dw > w || dt > t) continue;
+                    int64_t r = f[(size_t)(i + 1) * plane + (size_t)(w - dw) * (T + 1) + (size_t)(t - dt)];
+                    if (r >= INF) continue;
+                    if (I.phi[k] + r < best) best = I.phi[k] + r;
+                }
+                f[(size_t)i * plane + (size_t)w * (T + 1) + (size_t)t] = best;
+            }
+    int found = f[(size_t)0 * plane + (size_t)W * (T + 1) + (size_t)T] < INF;
+    if (found) {
+        int64_t w = W, t = T;
+        for (uint32_t i = 0; i < N; ++i) {
+            int64_t target = f[(size_t)i * plane + (size_t)w * (T + 1) + (size_t)t];
+            for (uint32_t c = 0; c < K; ++c) {
+                size_t k = (size_t)i * K + c;
+                if (!I.ok[k]) continue;
+                int64_t dw = I.mem[k] / gm, dt = I.tau[k] / gt;
+                if (dw > w || dt > t) continue;
+                int64_t r = f[(size_t)(i + 1) * plane + (size_t)(w - dw) * (T + 1) + (size_t)(t - dt)];
+                if (r < INF && I.phi[k] + r == target) { out_choice[i] = c; w -= dw; t -= dt; break; }
+            }
+        }
+        report(&I, out_choice, out_obj, out_mem, out_time);
+    }
+    (void)n;
+    free(f); inst_free(&I);
+    return found ? ORC_OK : ORC_INFEASIBLE;
+}
+
+/* Integer image of an instance, for tests that want to see phi / tau. */
+int orc_integerise(const double *risk, const int64_t *mem, const double *time,
+                   uint32_t N, uint32_t K, int64_t B_mem, double time_budget_sum,
+                   const uint8_t *forbidden, int64_t *phi, int64_t *tau, uint8_t *ok, int64_t *B_tau)
+{
+    int_instance I;
+    int rc = integerise(risk, mem, time, N, K, B_mem, time_budget_sum, forbidden, &I);
+    if (!rc) {
+        size_t n = (size_t)N * K;
+        memcpy(phi, I.phi, n * 8); memcpy(tau, I.tau, n * 8); memcpy(ok, I.ok, n);
+        *B_tau = I.B_tau;
+    }
+    inst_free(&I);
+    return rc;
+}
