@@ -1,0 +1,187 @@
+/*
+ * baoc.h -- C ABI of the BAOC gradient-stream profiler and allocator for
+ * AMD Instinct MI355X (gfx950).
+ *
+ * BAOC (Budget-Aware Optimizer Configurator) assigns one optimizer
+ * configuration to every parameter block under a memory and a time budget
+ * (Sec. 3, Algorithm 1).  This library is the data-parallel part of it:
+ *
+ *   baoc_profile_begin     describe the blocks B_i of a flat gradient buffer
+ *   baoc_profile_step      feed one sampled gradient g_t (one fused HBM pass)
+ *   baoc_profile_finalize  per-block metrics z_i and the risk table Phi[i][c]
+ *   baoc_allocate          exact solution of the allocation problem (Eq. 2)
+ *
+ * Conventions
+ *   - Every function returns a status (BAOC_OK = 0, errors negative).  On an
+ *     error no out-parameter has been written.
+ *   - "d_" arguments are DEVICE pointers (HIP, current device); all other
+ *     pointers are HOST pointers.
+ *   - The caller owns every buffer it passes in, including the device
+ *     workspace; the library owns only the opaque handle.
+ *   - A handle is not thread safe; different handles are independent.
+ *   - Every coordinate of a block is profiled (Omega_i = all of B_i).
+ */
+#ifndef BAOC_H
+#define BAOC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BAOC_OK                0
+#define BAOC_ERR_INVALID      (-1)  /* null pointer, empty or overlapping blocks, bad parameter */
+#define BAOC_ERR_WORKSPACE    (-2)  /* workspace too small or not 256-byte aligned */
+#define BAOC_ERR_UNSUPPORTED  (-3)  /* parameter value this build has no kernel for */
+#define BAOC_ERR_HIP          (-4)  /* HIP runtime error; sticky for the handle */
+#define BAOC_ERR_INFEASIBLE   (-5)  /* no assignment satisfies the budgets */
+#define BAOC_ERR_LIMIT        (-6)  /* solver node limit reached; no answer rather than a sub-optimal one */
+#define BAOC_ERR_STATE        (-7)  /* call out of order (finalize before any step, ...) */
+
+#define BAOC_GRAD_F32  0u
+#define BAOC_GRAD_BF16 1u
+
+/* One parameter block B_i (Sec. 3.1): numel = d_i coordinates starting `offset`
+ * elements into the flat gradient buffer.  Blocks may come in any order and
+ * leave gaps but must not overlap.  rows*cols == numel marks a matrix block
+ * (reserved for the structure residual of Eq. 7); otherwise both are 0. */
+typedef struct {
+    uint64_t offset;
+    uint64_t numel;
+    uint32_t rows, cols;
+} baoc_block;
+
+/* Profiler parameters.  baoc_profile_params_default() fills the defaults. */
+typedef struct {
+    float    beta_m;       /* EMA rate of the first moment, Eq. 3             (0.9)   */
+    float    beta_v;       /* EMA rate of the second moment, Eq. 3            (0.999) */
+    double   beta_rho;     /* smoothing of the direction stability, Eq. 5     (0.9)   */
+    double   eps;          /* epsilon of Sec. 3.3 / App. A.1                  (1e-12) */
+    float    eps_update;   /* epsilon inside u = m / (sqrt(v) + eps_update), Eq. 8 (1e-8) */
+    uint32_t quant_block;  /* coordinates per 8-bit absmax group; only 256 is built     */
+    uint32_t grad_dtype;   /* BAOC_GRAD_F32 | BAOC_GRAD_BF16 (states are always fp32)   */
+    uint32_t chunk_groups; /* quantisation groups per workgroup, 0 = library default    */
+} baoc_profile_params;
+
+/* A candidate configuration c = (y_a, y_m, y_d, y_f, b) of Def. 3.1:
+ * adaptive scaling, momentum, decoupled weight decay, factored state, bits. */
+typedef struct {
+    uint8_t y_a, y_m, y_d, y_f;
+    uint8_t bits;          /* 32 | 16 | 8 */
+} baoc_config;
+
+/* Normalisation anchors of App. A and the weights of Eq. 1 / Sec. 3.2. */
+typedef struct {
+    double gamma;                 /* weight of Agg(c), Eq. 1                  (0.1)      */
+    double A_low, A_high;         /* anisotropy anchors, Eq. 11               (ln 2, ln 10) */
+    double rho_low, rho_high;     /* direction anchors, Eq. 13                (0.2, 0.6) */
+    double eta_low, eta_high;     /* log(1+snr) anchors, Eq. 15               (0, 2)     */
+    int32_t use_snr_gate;         /* 1: s_M = s_rho * s_snr (Eq. 17); 0: s_M = s_rho     */
+    double lambda_pref;           /* soft preference strength, Sec. 3.2       (0)        */
+    const uint8_t* pref_mask;     /* n_configs flags marking C_pref, or NULL             */
+    const double*  C_raw;         /* n_blocks raw distortions C_i (Eq. 6), or NULL = 0   */
+    const double*  F_raw;         /* n_blocks raw structure residuals F_i (Eq. 7), or NULL = 0 */
+} baoc_risk_params;
+
+/* Per-block result of baoc_profile_finalize: raw metrics of Sec. 3.3 after the
+ * last step, their normalised signals (App. A), and the relative L2 error of
+ * storing the moment states in bf16 / block-wise 8 bit. */
+typedef struct {
+    uint64_t numel;
+    uint32_t steps;               /* sampled steps seen                                   */
+    uint32_t n_cos;               /* cosines folded into rho_bar (= steps - 1)            */
+    double rho_bar, cos_last;     /* Eq. 5 left: EMA of cos(g_t, g_{t-1}); the last cosine */
+    double snr;                   /* Eq. 5 right: |m|^2 / (|v|_1 + eps)                   */
+    double A, q10, q90;           /* Eq. 4 and the two quantiles of v it is built from    */
+    double Q16, Q8;               /* Eq. 8 after the clip of Eq. 10                       */
+    double lQ32, lQ16, lQ8;       /* Eq. 20: -log(Q + eps)                                */
+    double err_m16, err_v16, err_m8, err_v8;  /* |x^b - x|_2 / (|x|_2 + eps), x = m, v   */
+    double s_A, s_rho, s_snr, s_M, C_tilde, s_F;   /* App. A signals                      */
+    double m_sq, v_l1, g_sq_last; /* |m|^2, |v|_1, |g_T|^2                                */
+} baoc_block_stats;
+
+typedef struct baoc_profiler baoc_profiler;
+
+/* Defaults named in the paper (Sec. 3.2, Sec. 3.3, App. A) or, where it is
+ * silent, the values listed next to each field above. */
+void baoc_profile_params_default(baoc_profile_params* p);
+void baoc_risk_params_default(baoc_risk_params* p);
+
+/* Device workspace needed for this block layout: the fp32 states m, v (Eq. 3),
+ * the previous gradient (Eq. 5) in the gradient's dtype, per-workgroup partial
+ * sums, tables and the quantile scratch; roughly 12 (fp32 gradients) or 10
+ * (bf16) bytes per profiled coordinate.  blocks: HOST array of n_blocks. */
+int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
+                                 const baoc_profile_params* params, uint64_t* out_bytes);
+
+/* Validate the layout, carve `d_workspace` (DEVICE, 256-byte aligned, at least
+ * workspace_bytes long, owned by the caller and kept alive until
+ * baoc_profile_end) and zero the states.  Synchronous on the null stream.
+ * *out receives the handle.  Errors: INVALID, WORKSPACE, UNSUPPORTED, HIP. */
+int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
+                       const baoc_profile_params* params,
+                       void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out);
+
+/* One sampled step (Eq. 3, Eq. 5, Eq. 8): enqueue, on `hip_stream`
+ * (a hipStream_t, NULL = null stream), one fused pass over the flat gradient
+ * buffer `d_grad_flat` (DEVICE, grad_numel elements of the dtype given at
+ * begin) and the per-block reduction.  Returns without waiting.  The gradient
+ * buffer must stay valid until that stream work has run; afterwards the
+ * caller may overwrite it (the library keeps its own copy of g_t as g_{t-1}).
+ * Consecutive calls are consecutive samples.  Errors: INVALID (a block reaches
+ * beyond grad_numel, null pointer), HIP. */
+int baoc_profile_step(baoc_profiler* p, const void* d_grad_flat, uint64_t grad_numel,
+                      void* hip_stream);
+
+/* Metrics and risk table after the steps seen so far (Sec. 3.3, App. A, Eq. 9,
+ * Eq. 1): runs the quantile selection of Eq. 4 on `hip_stream`, waits for it,
+ * then fills out_stats (HOST, n_blocks entries, in the order given at begin)
+ * and out_risk (HOST, n_blocks x n_configs row-major,
+ * Phi[i][c] = R_i(c) - lambda_pref [c in C_pref] + gamma Agg(c)).
+ * Either output may be NULL.  The state is kept: more steps may follow and
+ * finalize may be called again with other configurations.
+ * Errors: INVALID (bits not in {8,16,32}, null configs with out_risk), STATE
+ * (no step yet), HIP. */
+int baoc_profile_finalize(baoc_profiler* p, const baoc_config* configs, uint32_t n_configs,
+                          const baoc_risk_params* risk_params,
+                          baoc_block_stats* out_stats, double* out_risk, void* hip_stream);
+
+/* Device views of one block's state inside the caller's workspace (for
+ * checkpoints and bit-level tests): d_m, d_v are fp32[numel]; d_g_prev holds
+ * numel elements of the gradient dtype.  Valid until baoc_profile_end. */
+int baoc_profile_state(const baoc_profiler* p, uint32_t block,
+                       const float** d_m, const float** d_v, const void** d_g_prev);
+
+/* Release the handle (host memory only; the workspace stays the caller's). */
+int baoc_profile_end(baoc_profiler* p);
+
+/* Exact solution of the allocation problem of Eq. 2 (a multiple-choice knapsack
+ * with a memory row and a time row) on the integer image of the instance:
+ *   phi = llround(1e9 * clamp(risk, -1e6, 1e6)),  tau = llround(1e6 * time_cost),
+ *   tau_budget = llround(1e6 * time_budget_sum).
+ * A pair (i,c) is excluded when forbidden[i*K+c] != 0 (hard constraint of
+ * Sec. 3.2) or when its risk or time cost is not finite.  Among the feasible
+ * assignments of least sum(phi) the lexicographically smallest choice vector
+ * is returned.  time_budget_sum bounds the SUM of r_{i,c_i}; the paper's
+ * mean form is B_time * n_blocks.  All pointers HOST; risk, mem_cost_bytes,
+ * time_cost, forbidden are n_blocks x n_configs row-major; out_choice has
+ * n_blocks entries; out_objective / out_mem / out_time may be NULL and receive
+ * sum(phi)/1e9, sum(mem) and sum(tau)/1e6 of the answer.
+ * Errors: INVALID (null, zero sizes, negative memory, NaN budget),
+ * INFEASIBLE, LIMIT. */
+int baoc_allocate(const double* risk, const int64_t* mem_cost_bytes, const double* time_cost,
+                  uint32_t n_blocks, uint32_t n_configs,
+                  int64_t mem_budget_bytes, double time_budget_sum,
+                  const uint8_t* forbidden,
+                  uint32_t* out_choice, double* out_objective, int64_t* out_mem, double* out_time);
+
+/* Search-node cap of baoc_allocate for this thread's later calls (0 = default). */
+void baoc_allocate_set_node_limit(uint64_t max_nodes);
+
+const char* baoc_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAOC_H */

@@ -209,7 +209,7 @@ int orc_block_step_bf16(orc_block *b, const uint16_t *g)
 }
 
 /* ------------------------------------------------------------------ */
-/* Finalize: raw metrics, normalisation (App. A) and risk (Eq. 11)     */
+/* Finalize: raw metrics, normalisation (App. A) and risk (Eq. 9)      */
 /* ------------------------------------------------------------------ */
 
 typedef struct {
@@ -227,9 +227,12 @@ typedef struct {
     double lambda_pref;
 } orc_risk_params;
 
+/* ascending; a NaN (only possible after a non-finite gradient) ranks above +inf */
 static int cmp_double(const void *a, const void *b)
 {
     double x = *(const double *)a, y = *(const double *)b;
+    int nx = isnan(x), ny = isnan(y);
+    if (nx || ny) return nx - ny;
     return (x > y) - (x < y);
 }
 
@@ -255,7 +258,7 @@ double orc_quantile(const float *x, uint64_t d, double q)
 
 static double clip(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-/* Eq. 8 then Eq. 12 (clip to [eps,1], NaN -> 0 first) */
+/* Eq. 8 then the clip of Eq. 10 (to [eps,1]; NaN -> 0 first) */
 static double cosine_Q(double U1, double U0, double U2, double eps)
 {
     double q = U1 / (sqrt(U0) * sqrt(U2) + eps);
@@ -288,7 +291,7 @@ int orc_block_finalize(const orc_block *b, const orc_risk_params *rp, double C_r
         o->A = log((o->q90 + eps) / (o->q10 + eps));
     }
 
-    /* Eq. 8, Eq. 12, Eq. 21 */
+    /* Eq. 8, Eq. 10 (clip), Eq. 20 (l_Q = -log(Q + eps)) */
     double Q32 = cosine_Q(b->U0, b->U0, b->U0, eps);
     o->Q16 = cosine_Q(b->U1[0], b->U0, b->U2[0], eps);
     o->Q8  = cosine_Q(b->U1[1], b->U0, b->U2[1], eps);
@@ -302,8 +305,8 @@ int orc_block_finalize(const orc_block *b, const orc_risk_params *rp, double C_r
     o->err_v16 = sqrt(b->Ev[0]) / (sqrt(b->S_vv) + eps);
     o->err_v8  = sqrt(b->Ev[1]) / (sqrt(b->S_vv) + eps);
 
-    /* App. A: Eq. 14 (s_A), Eq. 16 (s_rho), Eq. 18 (s_snr), Eq. 19 (s_M),
-       Eq. 20 (C-tilde), Eq. 21' (s_F) */
+    /* App. A: Eq. 12 (s_A), Eq. 14 (s_rho), Eq. 16 (s_snr), Eq. 17 (s_M),
+       Eq. 18 (C-tilde), Eq. 19 (s_F) */
     o->s_A   = clip((o->A - rp->A_low) / (rp->A_high - rp->A_low), 0.0, 1.0);
     o->s_rho = clip((o->rho_bar - rp->rho_low) / (rp->rho_high - rp->rho_low), 0.0, 1.0);
     o->s_snr = clip((log(1.0 + o->snr) - rp->eta_low) / (rp->eta_high - rp->eta_low), 0.0, 1.0);
@@ -319,7 +322,7 @@ double orc_agg(int y_a, int y_m, int y_d, int y_f, int bits)
     return (1 - y_a) + (1 - y_m) + (1 - y_d) + y_f + 32.0 / (double)bits - 1.0;
 }
 
-/* Eq. 11 with the soft preference of Sec. 3.2 and the regulariser of Eq. 1:
+/* Eq. 9 (= Eq. 21) with the soft preference of Sec. 3.2 and the regulariser of Eq. 1:
    Phi = R - lambda_pref [c in C_pref] + gamma Agg(c). cfg = (y_a,y_m,y_d,y_f,bits). */
 double orc_phi(const orc_stats *z, const uint8_t cfg[5], int preferred, const orc_risk_params *rp)
 {

@@ -1,0 +1,242 @@
+"""ctypes binding of libbaoc.so: argument marshalling only.
+
+Every step of the path runs inside the library (HIP kernels and its host
+code); PyTorch appears here only as the owner of device memory and streams.
+The library is loaded from the package directory and built with hipcc when it
+is not there; there is no fallback if it cannot be loaded.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+OK, ERR_INVALID, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP, ERR_INFEASIBLE, ERR_LIMIT, ERR_STATE = 0, -1, -2, -3, -4, -5, -6, -7
+GRAD_F32, GRAD_BF16 = 0, 1
+
+
+class Block(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("numel", C.c_uint64), ("rows", C.c_uint32), ("cols", C.c_uint32)]
+
+
+class ProfileParams(C.Structure):
+    _fields_ = [("beta_m", C.c_float), ("beta_v", C.c_float), ("beta_rho", C.c_double), ("eps", C.c_double),
+                ("eps_update", C.c_float), ("quant_block", C.c_uint32), ("grad_dtype", C.c_uint32),
+                ("chunk_groups", C.c_uint32)]
+
+
+class Config(C.Structure):
+    _fields_ = [("y_a", C.c_uint8), ("y_m", C.c_uint8), ("y_d", C.c_uint8), ("y_f", C.c_uint8), ("bits", C.c_uint8)]
+
+
+class RiskParams(C.Structure):
+    _fields_ = [("gamma", C.c_double), ("A_low", C.c_double), ("A_high", C.c_double),
+                ("rho_low", C.c_double), ("rho_high", C.c_double), ("eta_low", C.c_double), ("eta_high", C.c_double),
+                ("use_snr_gate", C.c_int32), ("lambda_pref", C.c_double),
+                ("pref_mask", C.c_void_p), ("C_raw", C.c_void_p), ("F_raw", C.c_void_p)]
+
+
+class BlockStats(C.Structure):
+    _fields_ = [("numel", C.c_uint64), ("steps", C.c_uint32), ("n_cos", C.c_uint32)] + [
+        (n, C.c_double) for n in (
+            "rho_bar", "cos_last", "snr", "A", "q10", "q90", "Q16", "Q8", "lQ32", "lQ16", "lQ8",
+            "err_m16", "err_v16", "err_m8", "err_v8", "s_A", "s_rho", "s_snr", "s_M", "C_tilde", "s_F",
+            "m_sq", "v_l1", "g_sq_last")]
+
+    def asdict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+STAT_FIELDS = [n for n, _ in BlockStats._fields_]
+
+
+class BaocError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree libbaoc.so, building it first only when no built library is there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_lib()
+    L = C.CDLL(_build.LIB)
+    vp, u32, u64, i64, f64 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int64, C.c_double
+    L.baoc_profile_params_default.argtypes = [C.POINTER(ProfileParams)]
+    L.baoc_profile_params_default.restype = None
+    L.baoc_risk_params_default.argtypes = [C.POINTER(RiskParams)]
+    L.baoc_risk_params_default.restype = None
+    L.baoc_profile_workspace_bytes.argtypes = [C.POINTER(Block), u32, C.POINTER(ProfileParams), C.POINTER(u64)]
+    L.baoc_profile_begin.argtypes = [C.POINTER(Block), u32, C.POINTER(ProfileParams), vp, u64, C.POINTER(vp)]
+    L.baoc_profile_step.argtypes = [vp, vp, u64, vp]
+    L.baoc_profile_finalize.argtypes = [vp, C.POINTER(Config), u32, C.POINTER(RiskParams),
+                                        C.POINTER(BlockStats), vp, vp]
+    L.baoc_profile_state.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+    L.baoc_profile_end.argtypes = [vp]
+    L.baoc_allocate.argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp, C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
+    L.baoc_allocate_set_node_limit.argtypes = [u64]
+    L.baoc_allocate_set_node_limit.restype = None
+    L.baoc_status_string.argtypes = [C.c_int]
+    L.baoc_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return load_library().baoc_status_string(int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise BaocError(rc, where)
+
+
+def default_profile_params(**kw):
+    p = ProfileParams()
+    load_library().baoc_profile_params_default(C.byref(p))
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def default_risk_params(**kw):
+    p = RiskParams()
+    load_library().baoc_risk_params_default(C.byref(p))
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def _block_array(blocks):
+    arr = (Block * len(blocks))()
+    for i, b in enumerate(blocks):
+        if isinstance(b, (tuple, list)):
+            o, n = int(b[0]), int(b[1])
+            r, c = (int(b[2]), int(b[3])) if len(b) >= 4 else (0, 0)
+        else:
+            o, n, r, c = int(b.offset), int(b.numel), int(getattr(b, "rows", 0)), int(getattr(b, "cols", 0))
+        arr[i] = Block(o, n, r, c)
+    return arr
+
+
+def workspace_bytes(blocks, params=None):
+    params = params or default_profile_params()
+    out = C.c_uint64()
+    arr = _block_array(blocks)
+    _check(load_library().baoc_profile_workspace_bytes(arr, len(blocks), C.byref(params), C.byref(out)),
+           "baoc_profile_workspace_bytes")
+    return out.value
+
+
+def config_array(configs):
+    arr = (Config * len(configs))()
+    for i, c in enumerate(configs):
+        arr[i] = Config(*[int(x) for x in c])
+    return arr
+
+
+class Profiler:
+    """baoc_profile_begin / step / finalize / end around a torch-owned workspace.
+
+    blocks: sequence of (offset, numel[, rows, cols]) or objects with those attributes.
+    """
+
+    def __init__(self, blocks, params=None, device="cuda:0", **kw):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        self.params = params or default_profile_params(**kw)
+        self.n_blocks = len(blocks)
+        self._blocks = _block_array(blocks)
+        nbytes = C.c_uint64()
+        _check(self.lib.baoc_profile_workspace_bytes(self._blocks, self.n_blocks, C.byref(self.params), C.byref(nbytes)),
+               "baoc_profile_workspace_bytes")
+        self.device = torch.device(device)
+        self.workspace = torch.empty(nbytes.value, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.baoc_profile_begin(self._blocks, self.n_blocks, C.byref(self.params),
+                                               self.workspace.data_ptr(), nbytes.value, C.byref(self._h)),
+                   "baoc_profile_begin")
+
+    def step(self, grad, stream=None):
+        """grad: flat torch tensor on the device, float32 or bfloat16 as given at begin."""
+        torch = self._torch
+        want = torch.float32 if self.params.grad_dtype == GRAD_F32 else torch.bfloat16
+        if grad.dtype != want or not grad.is_contiguous() or grad.device != self.device:
+            raise TypeError(f"gradient must be a contiguous {want} tensor on {self.device}")
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        _check(self.lib.baoc_profile_step(self._h, grad.data_ptr(), grad.numel(), s.cuda_stream), "baoc_profile_step")
+
+    def step_raw(self, d_ptr, numel, stream_handle):
+        return self.lib.baoc_profile_step(self._h, d_ptr, numel, stream_handle)
+
+    def finalize(self, configs=None, risk_params=None, pref_mask=None, C_raw=None, F_raw=None, stream=None):
+        """-> (stats: ctypes array of BlockStats, risk: float64 [N, K] or None)."""
+        torch = self._torch
+        rp = risk_params or default_risk_params()
+        keep = []
+        if pref_mask is not None:
+            a = np.ascontiguousarray(pref_mask, dtype=np.uint8); keep.append(a); rp.pref_mask = a.ctypes.data
+        if C_raw is not None:
+            a = np.ascontiguousarray(C_raw, dtype=np.float64); keep.append(a); rp.C_raw = a.ctypes.data
+        if F_raw is not None:
+            a = np.ascontiguousarray(F_raw, dtype=np.float64); keep.append(a); rp.F_raw = a.ctypes.data
+        stats = (BlockStats * self.n_blocks)()
+        K = 0 if configs is None else len(configs)
+        risk = np.zeros((self.n_blocks, K), np.float64) if K else None
+        cfg = config_array(configs) if K else None
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        _check(self.lib.baoc_profile_finalize(self._h, cfg, K, C.byref(rp), stats,
+                                              risk.ctypes.data if K else None, s.cuda_stream),
+               "baoc_profile_finalize")
+        return stats, risk
+
+    def state(self, block):
+        """(m, v, g_prev) of one block as torch views into the workspace."""
+        torch = self._torch
+        pm, pv, pg = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(self.lib.baoc_profile_state(self._h, block, C.byref(pm), C.byref(pv), C.byref(pg)), "baoc_profile_state")
+        base = self.workspace.data_ptr()
+        n = self._blocks[block].numel
+        gsz = 4 if self.params.grad_dtype == GRAD_F32 else 2
+        gdt = torch.float32 if gsz == 4 else torch.bfloat16
+
+        def view(ptr, dt, size):
+            off = ptr.value - base
+            return self.workspace[off:off + n * size].view(dt)
+        return view(pm, torch.float32, 4), view(pv, torch.float32, 4), view(pg, gdt, gsz)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self.lib.baoc_profile_end(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def allocate(risk, mem_cost_bytes, time_cost, mem_budget_bytes, time_budget_sum, forbidden=None):
+    """baoc_allocate -> (choice uint32[N], objective, mem, time). Raises BaocError on failure."""
+    risk = np.ascontiguousarray(risk, dtype=np.float64)
+    N, K = risk.shape
+    mem = np.ascontiguousarray(mem_cost_bytes, dtype=np.int64).reshape(N, K)
+    tc = np.ascontiguousarray(time_cost, dtype=np.float64).reshape(N, K)
+    fb = None if forbidden is None else np.ascontiguousarray(forbidden, dtype=np.uint8).reshape(N, K)
+    choice = np.zeros(N, np.uint32)
+    obj, om, ot = C.c_double(), C.c_int64(), C.c_double()
+    rc = load_library().baoc_allocate(risk.ctypes.data, mem.ctypes.data, tc.ctypes.data, N, K, int(mem_budget_bytes),
+                                      float(time_budget_sum), None if fb is None else fb.ctypes.data,
+                                      choice.ctypes.data, C.byref(obj), C.byref(om), C.byref(ot))
+    _check(rc, "baoc_allocate")
+    return choice, obj.value, om.value, ot.value

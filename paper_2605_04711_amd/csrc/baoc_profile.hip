@@ -1,0 +1,675 @@
+// Gradient-stream profiler of BAOC for gfx950 (MI355X): kernels and the
+// baoc_profile_* entry points.
+//
+// One sampled step is one streaming pass: every coordinate's gradient, previous
+// gradient and fp32 EMA states are read once and written once (28 B per
+// coordinate with fp32 gradients, 22 B with bf16), and everything Sec. 3.3 needs
+// from that coordinate is accumulated in registers on the way:
+//   Eq. 3  m <- beta_m m + (1-beta_m) g,  v <- beta_v v + (1-beta_v) g*g
+//   Eq. 5  <g_t, g_{t-1}>, |g_t|^2, |m|^2, |v|_1
+//   Eq. 8  update directions u = m/(sqrt(v)+eps_u) from the fp32 state and from
+//          the state after a bf16 or a block-wise absmax 8-bit round trip.
+// Work is cut into chunks that never straddle a parameter block; one workgroup
+// (4 wavefronts) owns a chunk, one wavefront owns a 256-coordinate quantisation
+// group at a time (4 coordinates per lane), so the group's absmax is a DPP
+// reduction inside the wavefront.  Sums go wavefront (DPP) -> workgroup (LDS)
+// -> one partial row per chunk -> per parameter block in fp64 (second kernel).
+// No float atomics anywhere: two runs give identical bits.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "baoc_internal.h"
+
+namespace baoc {
+
+struct alignas(8) Chunk {
+    uint64_t grad_start;    // element index into the caller's flat gradient buffer
+    uint64_t state_start;   // element index into m / v / g_prev (multiple of 256)
+    uint32_t count;         // coordinates in the chunk (only a block's last chunk may end off a multiple of 256)
+    uint32_t block;
+};
+
+struct alignas(8) BlockRow {
+    uint64_t state_start;
+    uint64_t numel;
+    uint32_t first_chunk, n_chunks;
+    uint64_t rank[4];       // order statistics wanted from v: lo(0.1), lo+1, lo(0.9), lo+1
+};
+
+struct StepConsts {
+    float beta_m, beta_v, om_m, om_v, eps_u;
+};
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// wavefront reductions on the DPP crossbar (64 lanes = 4 rows of 16)
+// ---------------------------------------------------------------------------
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp(float old, float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        __builtin_bit_cast(int, old), __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xf, false));
+}
+
+// quad_perm[1,0,3,2]=0xB1, quad_perm[2,3,0,1]=0x4E, row_ror:4=0x124, row_ror:8=0x128 leave every
+// lane of a row with the row's total; row_bcast:15 (0x142, rows 1 and 3) and row_bcast:31
+// (0x143, rows 2 and 3) carry the totals upwards so that lane 63 ends with the wavefront's.
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, dpp<0xB1, 0xf>(x, x));
+    x = fmaxf(x, dpp<0x4E, 0xf>(x, x));
+    x = fmaxf(x, dpp<0x124, 0xf>(x, x));
+    x = fmaxf(x, dpp<0x128, 0xf>(x, x));
+    x = fmaxf(x, dpp<0x142, 0xa>(x, x));
+    x = fmaxf(x, dpp<0x143, 0xc>(x, x));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+    x += dpp<0xB1, 0xf>(0.f, x);
+    x += dpp<0x4E, 0xf>(0.f, x);
+    x += dpp<0x124, 0xf>(0.f, x);
+    x += dpp<0x128, 0xf>(0.f, x);
+    x += dpp<0x142, 0xa>(0.f, x);
+    x += dpp<0x143, 0xc>(0.f, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// ---------------------------------------------------------------------------
+// element helpers
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_widen(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
+
+// round-to-nearest-even of a binary32 to the bf16 grid, result widened back
+__device__ __forceinline__ float bf16_round(float x)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+    uint32_t n = (u | 0x00400000u) & 0xffff0000u;
+    return __builtin_bit_cast(float, (u & 0x7fffffffu) > 0x7f800000u ? n : r);
+}
+
+// u = m / (sqrt(v) + eps_u) with the hardware's 1-ulp square root and reciprocal
+__device__ __forceinline__ float direction(float m, float v, float eps_u)
+{
+    return m * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v) + eps_u);
+}
+
+template <int GT> struct GradIO;
+
+template <> struct GradIO<BAOC_GRAD_F32> {
+    typedef float elem;
+    __device__ static __forceinline__ void load4(const elem* p, float g[4])
+    {
+        f4 t = *reinterpret_cast<const f4*>(p);
+        g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w;
+    }
+    __device__ static __forceinline__ float load1(const elem* p) { return *p; }
+    __device__ static __forceinline__ void store4(elem* p, const float g[4])
+    {
+        f4 t = {g[0], g[1], g[2], g[3]};
+        *reinterpret_cast<f4*>(p) = t;
+    }
+    static constexpr uintptr_t kAlignMask = 15;
+};
+
+template <> struct GradIO<BAOC_GRAD_BF16> {
+    typedef uint16_t elem;
+    __device__ static __forceinline__ void load4(const elem* p, float g[4])
+    {
+        u2 t = *reinterpret_cast<const u2*>(p);
+        g[0] = __builtin_bit_cast(float, t.x << 16); g[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
+        g[2] = __builtin_bit_cast(float, t.y << 16); g[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
+    }
+    __device__ static __forceinline__ float load1(const elem* p) { return bf16_widen(*p); }
+    // g holds exact bf16 values: the upper half of each word is the stored pattern
+    __device__ static __forceinline__ void store4(elem* p, const float g[4])
+    {
+        u2 t;
+        t.x = (__builtin_bit_cast(uint32_t, g[0]) >> 16) | (__builtin_bit_cast(uint32_t, g[1]) & 0xffff0000u);
+        t.y = (__builtin_bit_cast(uint32_t, g[2]) >> 16) | (__builtin_bit_cast(uint32_t, g[3]) & 0xffff0000u);
+        *reinterpret_cast<u2*>(p) = t;
+    }
+    static constexpr uintptr_t kAlignMask = 7;
+};
+
+// ---------------------------------------------------------------------------
+// the fused per-step pass
+// ---------------------------------------------------------------------------
+
+template <int GT>
+__global__ __launch_bounds__(256) void k_step(
+    const typename GradIO<GT>::elem* __restrict__ grad,
+    float* __restrict__ m_all, float* __restrict__ v_all,
+    typename GradIO<GT>::elem* __restrict__ gp_all,
+    const Chunk* __restrict__ chunks, float* __restrict__ partials, StepConsts k)
+{
+    typedef GradIO<GT> IO;
+    const Chunk ck = chunks[blockIdx.x];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t ngroups = (ck.count + (kQB - 1)) / kQB;
+    const typename IO::elem* gsrc = grad + ck.grad_start;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(gsrc) & IO::kAlignMask) == 0;
+
+    float acc[kNumSums];
+#pragma unroll
+    for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.f;
+
+    for (uint32_t grp = wave; grp < ngroups; grp += 4) {
+        const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
+        const uint64_t si = ck.state_start + e;           // states are padded to whole groups
+        float g[4], p[4], m[4], v[4];
+        {
+            f4 t = *reinterpret_cast<const f4*>(m_all + si);
+            m[0] = t.x; m[1] = t.y; m[2] = t.z; m[3] = t.w;
+            t = *reinterpret_cast<const f4*>(v_all + si);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        }
+        IO::load4(gp_all + si, p);
+        if (vec_ok && e + 4 <= ck.count) {
+            IO::load4(gsrc + e, g);
+        } else {                                          // ragged tail or unaligned block start
+#pragma unroll
+            for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
+        }
+
+        // Eq. 3 in fp32: the new term is rounded, then one fused multiply-add
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float tm = k.om_m * g[j];
+            const float tv = (k.om_v * g[j]) * g[j];
+            m[j] = __builtin_fmaf(k.beta_m, m[j], tm);
+            v[j] = __builtin_fmaf(k.beta_v, v[j], tv);
+        }
+        {
+            f4 t = {m[0], m[1], m[2], m[3]};
+            *reinterpret_cast<f4*>(m_all + si) = t;
+            f4 s = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f4*>(v_all + si) = s;
+        }
+        IO::store4(gp_all + si, g);
+
+        // group absmax of the 256 coordinates this wavefront holds
+        const float a_m = wave_max(fmaxf(fmaxf(fabsf(m[0]), fabsf(m[1])), fmaxf(fabsf(m[2]), fabsf(m[3]))));
+        const float a_v = wave_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+        // 8-bit code = rint(x * (L / a)) decided in fp32 with a correctly rounded quotient;
+        // an infinite scale (a == 0 or tiny) means all codes are 0
+        float s_m = 127.0f / a_m, s_v = 255.0f / a_v;
+        s_m = s_m < INFINITY ? s_m : 0.f;
+        s_v = s_v < INFINITY ? s_v : 0.f;
+        const float d_m = a_m * (1.0f / 127.0f), d_v = a_v * (1.0f / 255.0f);
+
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float mj = m[j], vj = v[j];
+            acc[S_GG] = __builtin_fmaf(g[j], g[j], acc[S_GG]);
+            acc[S_GP] = __builtin_fmaf(g[j], p[j], acc[S_GP]);
+            acc[S_MM] = __builtin_fmaf(mj, mj, acc[S_MM]);
+            acc[S_V1] += vj;
+            acc[S_VV] = __builtin_fmaf(vj, vj, acc[S_VV]);
+            const float u32 = direction(mj, vj, k.eps_u);
+            acc[U0] = __builtin_fmaf(u32, u32, acc[U0]);
+            {   // bf16 round trip
+                const float mb = bf16_round(mj), vb = bf16_round(vj);
+                const float ub = direction(mb, vb, k.eps_u);
+                const float du = ub - u32, dm = mb - mj, dv = vb - vj;
+                acc[U1_16] = __builtin_fmaf(u32, ub, acc[U1_16]);
+                acc[D_16] = __builtin_fmaf(du, du, acc[D_16]);
+                acc[U2_16] = __builtin_fmaf(ub, ub, acc[U2_16]);
+                acc[EM_16] = __builtin_fmaf(dm, dm, acc[EM_16]);
+                acc[EV_16] = __builtin_fmaf(dv, dv, acc[EV_16]);
+            }
+            {   // block-wise absmax 8-bit round trip
+                const float mb = __builtin_rintf(mj * s_m) * d_m;
+                const float vb = __builtin_rintf(vj * s_v) * d_v;
+                const float ub = direction(mb, vb, k.eps_u);
+                const float du = ub - u32, dm = mb - mj, dv = vb - vj;
+                acc[U1_8] = __builtin_fmaf(u32, ub, acc[U1_8]);
+                acc[D_8] = __builtin_fmaf(du, du, acc[D_8]);
+                acc[U2_8] = __builtin_fmaf(ub, ub, acc[U2_8]);
+                acc[EM_8] = __builtin_fmaf(dm, dm, acc[EM_8]);
+                acc[EV_8] = __builtin_fmaf(dv, dv, acc[EV_8]);
+            }
+        }
+    }
+
+    // wavefront -> LDS -> one partial row per chunk, in a fixed order
+    __shared__ float red[4][kNumSums];
+#pragma unroll
+    for (int i = 0; i < (int)kNumSums; ++i) {
+        const float s = wave_sum(acc[i]);
+        if (lane == 0) red[wave][i] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < kNumSums) {
+        const float s = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+        partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] = s;
+    }
+}
+
+// Second stage: one workgroup per parameter block adds that block's partial rows in fp64,
+// then folds the step into the running direction stability (Eq. 5, left):
+//   cos_t = <g_t,g_{t-1}> / (|g_t| |g_{t-1}| + eps), NaN -> 0 (App. A.1);
+//   the first cosine initialises rho_bar, later ones enter with weight 1 - beta_rho.
+__global__ __launch_bounds__(256) void k_block_reduce(
+    const float* __restrict__ partials, const BlockRow* __restrict__ rows,
+    double* __restrict__ rec_all, uint32_t step, double beta_rho, double eps)
+{
+    const BlockRow br = rows[blockIdx.x];
+    double acc[kNumSums];
+#pragma unroll
+    for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.0;
+    for (uint32_t c = threadIdx.x; c < br.n_chunks; c += 256) {
+        const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(br.first_chunk + c) * kNumSums);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f4 t = row[q];
+            acc[4 * q + 0] += (double)t.x; acc[4 * q + 1] += (double)t.y;
+            acc[4 * q + 2] += (double)t.z; acc[4 * q + 3] += (double)t.w;
+        }
+    }
+    __shared__ double sh[256];
+    double* rec = rec_all + (uint64_t)blockIdx.x * kRecDoubles;
+#pragma unroll 1
+    for (int i = 0; i < (int)kNumSums; ++i) {
+        sh[threadIdx.x] = acc[i];
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) rec[i] = sh[0];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double S_gg = rec[S_GG], S_gp = rec[S_GP];
+        if (step >= 2) {
+            double c = S_gp / (sqrt(S_gg) * sqrt(rec[R_SPP]) + eps);
+            if (c != c) c = 0.0;
+            const double n = rec[R_NCOS];
+            rec[R_RHO] = (n == 0.0) ? c : beta_rho * rec[R_RHO] + (1.0 - beta_rho) * c;
+            rec[R_COS] = c;
+            rec[R_NCOS] = n + 1.0;
+        }
+        rec[R_SPP] = S_gg;
+        rec[R_STEPS] = (double)step;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 4: exact order statistics of v per block by a three-pass radix selection
+// on the bit patterns (v >= 0, so the pattern order is the value order).
+// Digits: bits 30..20, 19..9, 8..0.  Four ranks per block share every pass.
+// ---------------------------------------------------------------------------
+
+__global__ void k_fill_u32(uint32_t* p, uint64_t n, uint32_t val)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) p[i] = val;
+}
+
+constexpr uint32_t kBins = 2048;
+
+template <int PASS>
+__global__ __launch_bounds__(256) void k_hist(
+    const float* __restrict__ v_all, const Chunk* __restrict__ chunks,
+    const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all)
+{
+    constexpr int NT = PASS == 1 ? 1 : 4;
+    __shared__ uint32_t h[NT * kBins];
+    const Chunk ck = chunks[blockIdx.x];
+    for (uint32_t i = threadIdx.x; i < NT * kBins; i += 256) h[i] = 0;
+    uint32_t pre[4] = {0, 0, 0, 0};
+    if (PASS > 1) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) pre[t] = sel_prefix[ck.block * 4 + t];
+    }
+    __syncthreads();
+    const uint32_t* bits = reinterpret_cast<const uint32_t*>(v_all + ck.state_start);
+    for (uint32_t e = threadIdx.x * 4; e < ck.count; e += 1024) {
+        typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+        const u4 w = *reinterpret_cast<const u4*>(bits + e);        // padded state: always in bounds
+        const uint32_t key[4] = {w.x & 0x7fffffffu, w.y & 0x7fffffffu, w.z & 0x7fffffffu, w.w & 0x7fffffffu};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (e + j >= ck.count) break;
+            if (PASS == 1) {
+                atomicAdd(&h[key[j] >> 20], 1u);
+            } else {
+                const uint32_t hi = PASS == 2 ? key[j] >> 20 : key[j] >> 9;
+                const uint32_t bin = PASS == 2 ? (key[j] >> 9) & 0x7ffu : key[j] & 0x1ffu;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (hi == pre[t]) atomicAdd(&h[t * kBins + bin], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* out = hist_all + (uint64_t)ck.block * 4 * kBins;
+    for (uint32_t i = threadIdx.x; i < NT * kBins; i += 256)
+        if (h[i]) atomicAdd(&out[i], h[i]);
+}
+
+// One thread per (block, rank): walk the histogram to the bin that holds the rank,
+// extend the key prefix by that digit and keep the rank inside the bin.
+template <int PASS>
+__global__ void k_pick(const uint32_t* __restrict__ hist_all, const BlockRow* __restrict__ rows,
+                       uint32_t* __restrict__ sel_prefix, uint64_t* __restrict__ sel_rank,
+                       float* __restrict__ order_stat, uint32_t n_blocks)
+{
+    const uint32_t id = blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= n_blocks * 4) return;
+    const uint32_t b = id >> 2, t = id & 3;
+    const uint32_t* h = hist_all + ((uint64_t)b * 4 + (PASS == 1 ? 0 : t)) * kBins;
+    uint64_t r = PASS == 1 ? rows[b].rank[t] : sel_rank[id];
+    const uint32_t nb = PASS == 3 ? 512 : kBins;
+    uint32_t bin = 0;
+    for (; bin + 1 < nb; ++bin) {
+        const uint32_t c = h[bin];
+        if (r < c) break;
+        r -= c;
+    }
+    const uint32_t prefix = PASS == 1 ? bin : ((sel_prefix[id] << (PASS == 2 ? 11 : 9)) | bin);
+    sel_prefix[id] = prefix;
+    sel_rank[id] = r;
+    if (PASS == 3) order_stat[id] = __builtin_bit_cast(float, prefix);
+}
+
+}  // namespace baoc
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+using namespace baoc;
+
+struct Plan {
+    std::vector<Chunk> chunks;
+    std::vector<BlockRow> rows;
+    uint64_t padded = 0;          // coordinates in m / v / g_prev
+    uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
+             off_rec = 0, off_hist = 0, off_selp = 0, off_selr = 0, off_ostat = 0, total = 0;
+};
+
+struct baoc_profiler {
+    baoc_profile_params params;
+    Plan plan;
+    std::vector<baoc_block> blocks;
+    char* ws = nullptr;
+    uint32_t steps = 0;
+    uint64_t max_end = 0;         // largest offset + numel over the blocks
+    int sticky = BAOC_OK;
+    std::vector<double> h_rec;
+    std::vector<float> h_ostat;
+};
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+static int check_params(const baoc_profile_params* p)
+{
+    if (!p) return BAOC_ERR_INVALID;
+    if (!(p->beta_m > 0.f && p->beta_m < 1.f) || !(p->beta_v > 0.f && p->beta_v < 1.f)) return BAOC_ERR_INVALID;
+    if (!(p->beta_rho >= 0.0 && p->beta_rho < 1.0)) return BAOC_ERR_INVALID;
+    if (!(p->eps >= 0.0) || !(p->eps_update >= 0.f)) return BAOC_ERR_INVALID;
+    if (p->grad_dtype != BAOC_GRAD_F32 && p->grad_dtype != BAOC_GRAD_BF16) return BAOC_ERR_INVALID;
+    if (p->quant_block != kQB) return BAOC_ERR_UNSUPPORTED;
+    if (p->chunk_groups > 4096) return BAOC_ERR_INVALID;
+    return BAOC_OK;
+}
+
+static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_params* prm, Plan* out, uint64_t* max_end)
+{
+    if (!blocks || n == 0) return BAOC_ERR_INVALID;
+    int rc = check_params(prm);
+    if (rc) return rc;
+    // no overlap: sort a copy by offset
+    std::vector<std::pair<uint64_t, uint64_t>> iv(n);
+    uint64_t end_max = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const baoc_block& b = blocks[i];
+        if (b.numel == 0) return BAOC_ERR_INVALID;
+        if (b.numel > 0xffffffffull) return BAOC_ERR_UNSUPPORTED;      // 32-bit histogram counters
+        if (b.offset + b.numel < b.offset) return BAOC_ERR_INVALID;
+        if ((b.rows || b.cols) && (uint64_t)b.rows * b.cols != b.numel) return BAOC_ERR_INVALID;
+        iv[i] = {b.offset, b.numel};
+        end_max = std::max(end_max, b.offset + b.numel);
+    }
+    std::sort(iv.begin(), iv.end());
+    for (uint32_t i = 1; i < n; ++i)
+        if (iv[i - 1].first + iv[i - 1].second > iv[i].first) return BAOC_ERR_INVALID;
+    if (max_end) *max_end = end_max;
+
+    const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : kDefaultChunkGroups;
+    Plan& P = *out;
+    P.chunks.clear(); P.rows.resize(n);
+    uint64_t state = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const baoc_block& b = blocks[i];
+        const uint64_t groups = (b.numel + kQB - 1) / kQB;
+        const uint64_t nch = (groups + cg - 1) / cg;
+        const uint64_t per = (groups + nch - 1) / nch;               // balanced, whole groups
+        BlockRow& r = P.rows[i];
+        r.state_start = state; r.numel = b.numel;
+        r.first_chunk = (uint32_t)P.chunks.size();
+        uint64_t g0 = 0;
+        while (g0 < groups) {
+            const uint64_t g1 = std::min(groups, g0 + per);
+            Chunk c;
+            c.grad_start = b.offset + g0 * kQB;
+            c.state_start = state + g0 * kQB;
+            c.count = (uint32_t)(std::min<uint64_t>(b.numel, g1 * kQB) - g0 * kQB);
+            c.block = i;
+            P.chunks.push_back(c);
+            g0 = g1;
+        }
+        r.n_chunks = (uint32_t)P.chunks.size() - r.first_chunk;
+        for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
+            const double pos = (q == 0 ? 0.1 : 0.9) * (double)(b.numel - 1);
+            const uint64_t lo = (uint64_t)std::floor(pos);
+            r.rank[2 * q] = lo;
+            r.rank[2 * q + 1] = std::min<uint64_t>(lo + 1, b.numel - 1);
+        }
+        state += groups * kQB;
+        if (P.chunks.size() > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
+    }
+    P.padded = state;
+    const uint64_t gsz = prm->grad_dtype == BAOC_GRAD_F32 ? 4 : 2;
+    uint64_t o = 0;
+    P.off_m = o;        o = align_up(o + P.padded * 4, 256);
+    P.off_v = o;        o = align_up(o + P.padded * 4, 256);
+    P.off_gp = o;       o = align_up(o + P.padded * gsz, 256);
+    P.off_partials = o; o = align_up(o + P.chunks.size() * kNumSums * 4, 256);
+    P.off_chunks = o;   o = align_up(o + P.chunks.size() * sizeof(Chunk), 256);
+    P.off_rows = o;     o = align_up(o + (uint64_t)n * sizeof(BlockRow), 256);
+    P.off_rec = o;      o = align_up(o + (uint64_t)n * kRecDoubles * 8, 256);
+    P.off_hist = o;     o = align_up(o + (uint64_t)n * 4 * kBins * 4, 256);
+    P.off_selp = o;     o = align_up(o + (uint64_t)n * 4 * 4, 256);
+    P.off_selr = o;     o = align_up(o + (uint64_t)n * 4 * 8, 256);
+    P.off_ostat = o;    o = align_up(o + (uint64_t)n * 4 * 4, 256);
+    P.total = o;
+    return BAOC_OK;
+}
+
+extern "C" void baoc_profile_params_default(baoc_profile_params* p)
+{
+    if (!p) return;
+    p->beta_m = 0.9f; p->beta_v = 0.999f; p->beta_rho = 0.9; p->eps = 1e-12; p->eps_update = 1e-8f;
+    p->quant_block = kQB; p->grad_dtype = BAOC_GRAD_F32; p->chunk_groups = 0;
+}
+
+extern "C" int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
+                                            const baoc_profile_params* params, uint64_t* out_bytes)
+{
+    if (!out_bytes) return BAOC_ERR_INVALID;
+    Plan P;
+    int rc = make_plan(blocks, n_blocks, params, &P, nullptr);
+    if (rc) return rc;
+    *out_bytes = P.total;
+    return BAOC_OK;
+}
+
+extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
+                                  const baoc_profile_params* params,
+                                  void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out)
+{
+    if (!out || !d_workspace) return BAOC_ERR_INVALID;
+    baoc_profiler* h = new (std::nothrow) baoc_profiler();
+    if (!h) return BAOC_ERR_INVALID;
+    int rc = make_plan(blocks, n_blocks, params, &h->plan, &h->max_end);
+    if (rc) { delete h; return rc; }
+    if (workspace_bytes < h->plan.total || (reinterpret_cast<uintptr_t>(d_workspace) & 255)) { delete h; return BAOC_ERR_WORKSPACE; }
+    h->params = *params;
+    h->blocks.assign(blocks, blocks + n_blocks);
+    h->ws = static_cast<char*>(d_workspace);
+    const Plan& P = h->plan;
+    hipError_t e = hipMemset(h->ws, 0, P.total);
+    if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_chunks, P.chunks.data(), P.chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_rows, P.rows.data(), P.rows.size() * sizeof(BlockRow), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) { (void)hipGetLastError(); delete h; return BAOC_ERR_HIP; }
+    h->h_rec.resize((size_t)n_blocks * kRecDoubles);
+    h->h_ostat.resize((size_t)n_blocks * 4);
+    *out = h;
+    return BAOC_OK;
+}
+
+extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint64_t grad_numel, void* hip_stream)
+{
+    if (!h || !d_grad_flat) return BAOC_ERR_INVALID;
+    if (h->sticky) return h->sticky;
+    if (grad_numel < h->max_end) return BAOC_ERR_INVALID;
+    const Plan& P = h->plan;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const baoc_profile_params& q = h->params;
+    StepConsts k{q.beta_m, q.beta_v, 1.0f - q.beta_m, 1.0f - q.beta_v, q.eps_update};
+    float* m = reinterpret_cast<float*>(h->ws + P.off_m);
+    float* v = reinterpret_cast<float*>(h->ws + P.off_v);
+    const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
+    float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
+    const uint32_t grid = (uint32_t)P.chunks.size();
+    if (q.grad_dtype == BAOC_GRAD_F32)
+        hipLaunchKernelGGL(k_step<BAOC_GRAD_F32>, dim3(grid), dim3(256), 0, st,
+                           static_cast<const float*>(d_grad_flat), m, v, reinterpret_cast<float*>(h->ws + P.off_gp), ch, part, k);
+    else
+        hipLaunchKernelGGL(k_step<BAOC_GRAD_BF16>, dim3(grid), dim3(256), 0, st,
+                           static_cast<const uint16_t*>(d_grad_flat), m, v, reinterpret_cast<uint16_t*>(h->ws + P.off_gp), ch, part, k);
+    h->steps += 1;
+    hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(256), 0, st,
+                       part, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
+                       reinterpret_cast<double*>(h->ws + P.off_rec), h->steps, q.beta_rho, q.eps);
+    if (hipGetLastError() != hipSuccess) { h->sticky = BAOC_ERR_HIP; return BAOC_ERR_HIP; }
+    return BAOC_OK;
+}
+
+extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* configs, uint32_t n_configs,
+                                     const baoc_risk_params* risk_params,
+                                     baoc_block_stats* out_stats, double* out_risk, void* hip_stream)
+{
+    if (!h) return BAOC_ERR_INVALID;
+    if (h->sticky) return h->sticky;
+    if (h->steps == 0) return BAOC_ERR_STATE;
+    if (out_risk && (!configs || n_configs == 0)) return BAOC_ERR_INVALID;
+    for (uint32_t c = 0; out_risk && c < n_configs; ++c) {
+        const baoc_config& k = configs[c];
+        if ((k.bits != 32 && k.bits != 16 && k.bits != 8) || k.y_a > 1 || k.y_m > 1 || k.y_d > 1 || k.y_f > 1) return BAOC_ERR_INVALID;
+    }
+    baoc_risk_params rp;
+    if (risk_params) rp = *risk_params; else baoc_risk_params_default(&rp);
+    if (!(rp.A_high != rp.A_low) || !(rp.rho_high != rp.rho_low) || !(rp.eta_high != rp.eta_low)) return BAOC_ERR_INVALID;
+
+    const Plan& P = h->plan;
+    const uint32_t N = (uint32_t)P.rows.size(), nch = (uint32_t)P.chunks.size();
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const float* v = reinterpret_cast<const float*>(h->ws + P.off_v);
+    const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
+    const BlockRow* rows = reinterpret_cast<const BlockRow*>(h->ws + P.off_rows);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(h->ws + P.off_hist);
+    uint32_t* selp = reinterpret_cast<uint32_t*>(h->ws + P.off_selp);
+    uint64_t* selr = reinterpret_cast<uint64_t*>(h->ws + P.off_selr);
+    float* ostat = reinterpret_cast<float*>(h->ws + P.off_ostat);
+    const uint64_t hist_words = (uint64_t)N * 4 * kBins;
+    const uint32_t fill_grid = (uint32_t)std::min<uint64_t>((hist_words + 255) / 256, 4096);
+    const uint32_t pick_grid = (N * 4 + 63) / 64;
+
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
+    hipLaunchKernelGGL(k_hist<1>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
+    hipLaunchKernelGGL(k_pick<1>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
+    hipLaunchKernelGGL(k_hist<2>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
+    hipLaunchKernelGGL(k_pick<2>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
+    hipLaunchKernelGGL(k_hist<3>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
+    hipLaunchKernelGGL(k_pick<3>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(h->h_rec.data(), h->ws + P.off_rec, h->h_rec.size() * 8, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(h->h_ostat.data(), ostat, h->h_ostat.size() * 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { (void)hipGetLastError(); h->sticky = BAOC_ERR_HIP; return BAOC_ERR_HIP; }
+
+    std::vector<baoc_block_stats> stats(N);
+    for (uint32_t i = 0; i < N; ++i) {
+        RawBlock r;
+        const double* rec = &h->h_rec[(size_t)i * kRecDoubles];
+        r.numel = P.rows[i].numel;
+        for (int s = 0; s < (int)kNumSums; ++s) r.sums[s] = rec[s];
+        r.rho_bar = rec[R_RHO]; r.cos_last = rec[R_COS];
+        r.n_cos = (uint32_t)rec[R_NCOS]; r.steps = (uint32_t)rec[R_STEPS];
+        for (int t = 0; t < 4; ++t) r.order_stat[t] = h->h_ostat[(size_t)i * 4 + t];
+        const double p10 = 0.1 * (double)(r.numel - 1), p90 = 0.9 * (double)(r.numel - 1);
+        r.frac10 = p10 - std::floor(p10); r.frac90 = p90 - std::floor(p90);
+        block_metrics(r, h->params.eps, rp, rp.C_raw ? rp.C_raw[i] : 0.0, rp.F_raw ? rp.F_raw[i] : 0.0, &stats[i]);
+    }
+    if (out_stats) std::memcpy(out_stats, stats.data(), sizeof(baoc_block_stats) * N);
+    if (out_risk)
+        for (uint32_t i = 0; i < N; ++i)
+            for (uint32_t c = 0; c < n_configs; ++c)
+                out_risk[(size_t)i * n_configs + c] =
+                    config_phi(stats[i], configs[c], rp.pref_mask && rp.pref_mask[c], rp);
+    return BAOC_OK;
+}
+
+extern "C" int baoc_profile_state(const baoc_profiler* h, uint32_t block,
+                                  const float** d_m, const float** d_v, const void** d_g_prev)
+{
+    if (!h || block >= h->plan.rows.size()) return BAOC_ERR_INVALID;
+    const Plan& P = h->plan;
+    const uint64_t s = P.rows[block].state_start;
+    const uint64_t gsz = h->params.grad_dtype == BAOC_GRAD_F32 ? 4 : 2;
+    if (d_m) *d_m = reinterpret_cast<const float*>(h->ws + P.off_m) + s;
+    if (d_v) *d_v = reinterpret_cast<const float*>(h->ws + P.off_v) + s;
+    if (d_g_prev) *d_g_prev = h->ws + P.off_gp + s * gsz;
+    return BAOC_OK;
+}
+
+extern "C" int baoc_profile_end(baoc_profiler* h)
+{
+    if (!h) return BAOC_ERR_INVALID;
+    delete h;
+    return BAOC_OK;
+}
+
+extern "C" const char* baoc_status_string(int s)
+{
+    switch (s) {
+    case BAOC_OK: return "ok";
+    case BAOC_ERR_INVALID: return "invalid argument";
+    case BAOC_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case BAOC_ERR_UNSUPPORTED: return "unsupported parameter";
+    case BAOC_ERR_HIP: return "HIP runtime error";
+    case BAOC_ERR_INFEASIBLE: return "no assignment satisfies the budgets";
+    case BAOC_ERR_LIMIT: return "solver node limit reached";
+    case BAOC_ERR_STATE: return "call out of order";
+    default: return "unknown status";
+    }
+}

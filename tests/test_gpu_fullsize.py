@@ -1,0 +1,34 @@
+"""Full-size layouts in the launch configuration the benchmark times; the oracle follows a sample
+of blocks (every small block, the largest ones, a seeded 10 % draw).  The window is shortened to
+keep the CPU side within minutes; blocks are independent, so a sampled block is checked exactly."""
+import numpy as np
+import pytest
+
+from synth import workloads as W
+from test_gpu_parity import env, run_both  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_blocks(w, small=300_000, n_large=2, frac=0.1, cap=60_000_000, seed=11):
+    rng = np.random.default_rng(seed)
+    order = np.argsort([-b.numel for b in w.blocks])
+    pick = set(int(i) for i in order[:n_large])
+    pick |= {i for i, b in enumerate(w.blocks) if b.numel <= small}
+    for i in rng.permutation(len(w.blocks))[:max(1, int(frac * len(w.blocks)))]:
+        pick.add(int(i))
+    out, total = [], 0
+    for i in sorted(pick, key=lambda i: -w.blocks[i].numel if i in set(int(j) for j in order[:n_large]) else w.blocks[i].numel):
+        if total + w.blocks[i].numel > cap and i not in set(int(j) for j in order[:n_large]):
+            continue
+        out.append(i); total += w.blocks[i].numel
+    return sorted(out)
+
+
+@pytest.mark.parametrize("name,T", [("unet", 6), ("gpt_1p3b", 4), ("llama7b", 3)])
+def test_fullsize_sampled_blocks(env, name, T):  # noqa: F811
+    w = W.make(name)
+    only = sample_blocks(w)
+    print(f"{name}: oracle follows {len(only)} of {len(w.blocks)} blocks, "
+          f"{sum(w.blocks[i].numel for i in only):,} of {w.numel:,} coordinates, T={T}", flush=True)
+    run_both(env, w, T, only=only, check_state=False)

@@ -1,0 +1,169 @@
+"""HIP path against the CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import (OracleRunner, assert_risk_close, assert_stats_close, oracle_params, to_host_bits)
+from synth import workloads as W
+
+pytestmark = pytest.mark.gpu
+SEED = 1
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import paper_2605_04711_amd as B
+    from paper_2605_04711_amd import binding
+    from synth import device
+    B.load_library(); device.lib()
+    return dict(torch=torch, B=B, binding=binding, device=device)
+
+
+def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED):
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=chunk_groups)
+    prof = binding.Profiler(w.blocks, params)
+    orc = OracleRunner(w.blocks, only, **oracle_params(params))
+    buf = device.new_buffer(w)
+    for t in range(1, T + 1):
+        device.fill(w, buf, seed, t)
+        prof.step(buf)
+        orc.step_from_device(buf)
+    stats, risk = prof.finalize(w.configs)
+    ostats, orisk = orc.finalize(w.configs)
+    for row, i in enumerate(orc.only):
+        assert_stats_close(stats[i], ostats[i], f"{w.name} block {i} ({w.blocks[i].name}, d={w.blocks[i].numel})")
+        assert_risk_close(risk[i], orisk[row], f"{w.name} block {i}")
+        if check_state:
+            m, v, p = prof.state(i)
+            ob = orc.state[i]
+            assert np.array_equal(to_host_bits(m).view(np.uint32), ob.m.view(np.uint32)), f"m bits, block {i}"
+            assert np.array_equal(to_host_bits(v).view(np.uint32), ob.v.view(np.uint32)), f"v bits, block {i}"
+            gp = to_host_bits(p)
+            want = ob.p if gp.dtype == np.float32 else (ob.p.view(np.uint32) >> 16).astype(np.uint16)
+            assert np.array_equal(gp.view(want.dtype), want), f"g_prev bits, block {i}"
+    torch.cuda.synchronize()
+    return prof, stats, risk, ostats, orisk
+
+
+def test_tiny_all_blocks_all_steps_and_allocation(env):
+    B = env["B"]
+    w = W.make("tiny")
+    prof, stats, risk, ostats, orisk = run_both(env, w, w.T)
+    mem, tc, bm, cap = W.allocation_inputs(w)
+    cap = 1e9 if not np.isfinite(cap) else cap
+    x, obj, m, t = B.allocate(risk, mem, tc, bm, cap)
+    rc, ox, oobj, om, ot = oracle.allocate_brute(risk, mem, tc, bm, cap)          # same risk table: bit exact
+    assert rc == 0 and list(x) == list(ox) and obj == oobj and m == om and t == ot
+    rc, ox2, *_ = oracle.allocate_brute(orisk, mem, tc, bm, cap)
+    assert rc == 0 and m <= bm
+
+
+def test_tiny_bf16_gradients(env):
+    w = W.make("tiny"); w.grad_dtype = "bf16"
+    run_both(env, w, 6)
+
+
+def ragged_workload(dtype, pad, reverse=False):
+    sizes = [1, 3, 63, 64, 255, 256, 257, 1000, 4099, 9408, 70001, 5, 1024 * 33 + 7]
+    blocks = [W.BlockSpec(f"r{i}", n) for i, n in enumerate(sizes)]
+    w = W.Workload("ragged", blocks, 5, dtype, "cycle", **W.K6)
+    W.layout(w, pad); W.draw_stream_params(w, 5)
+    if reverse:
+        w.blocks.reverse()
+    return w
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pad,chunk_groups,reverse", [(1, 2, False), (64, 0, True), (3, 1, False)])
+def test_ragged_blocks_unaligned_offsets_gaps_and_order(env, dtype, pad, chunk_groups, reverse):
+    run_both(env, ragged_workload(dtype, pad, reverse), 5, chunk_groups=chunk_groups)
+
+
+def test_resnet50_all_blocks_all_steps(env):
+    w = W.make("resnet50")
+    run_both(env, w, w.T)
+
+
+def test_gpt2_small_all_steps(env):
+    w = W.make("gpt2_small")
+    only = [i for i, b in enumerate(w.blocks) if b.numel < 3_000_000]          # everything but the two embeddings
+    run_both(env, w, w.T, only=only, check_state=False)
+
+
+def test_gpt2_small_embeddings_heavy_tailed(env):
+    w = W.make("gpt2_small")
+    run_both(env, w, 4, only=[0, 1])
+
+
+def test_two_runs_give_identical_bits(env):
+    w = ragged_workload("f32", 1)
+    a = run_both(env, w, 4, chunk_groups=2)[1]
+    b = run_both(env, w, 4, chunk_groups=2)[1]
+    assert bytes(a) == bytes(b)
+
+
+def test_constant_gradient_direction_is_one_and_snr_closed_form(env):
+    torch, binding = env["torch"], env["binding"]
+    n = 100_003
+    g = torch.randn(n, device="cuda:0")
+    prof = binding.Profiler([(0, n)])
+    for _ in range(16):
+        prof.step(g)
+    st = prof.finalize()[0][0]
+    bm, bv = float(np.float32(0.9)), float(np.float32(0.999))
+    assert st.rho_bar == pytest.approx(1.0, abs=1e-9)
+    assert st.snr == pytest.approx((1 - bm ** 16) ** 2 / (1 - bv ** 16), rel=1e-4)
+    assert st.n_cos == 15 and st.steps == 16
+
+
+def test_other_blocks_do_not_matter(env):
+    torch, binding = env["torch"], env["binding"]
+    blocks = [(0, 5000), (5003, 777), (6000, 30000)]
+    g = [torch.randn(36000, device="cuda:0") for _ in range(3)]
+    a = binding.Profiler(blocks); b = binding.Profiler([blocks[1]])
+    for t in g:
+        a.step(t)
+        u = t.clone(); u[:5003] = 3.0; u[5780:] = -1.0
+        b.step(u)
+    sa, sb = a.finalize()[0][1], b.finalize()[0][0]
+    assert bytes(sa) == bytes(sb)
+
+
+def test_nan_gradient_poisons_only_its_block(env):
+    torch, binding = env["torch"], env["binding"]
+    blocks = [(0, 1000), (1024, 1000)]
+    g = torch.randn(2048, device="cuda:0"); g[5] = float("nan")
+    a = binding.Profiler(blocks)
+    a.step(g); a.step(g)
+    s = a.finalize()[0]
+    assert np.isnan(s[0].m_sq) and np.isfinite(s[1].m_sq) and np.isfinite(s[1].lQ8) and s[1].rho_bar == pytest.approx(1.0)
+    o = oracle.Block(1000); h = to_host_bits(g[:1000]); o.step(h); o.step(h)
+    assert_stats_close(s[0], o.finalize(), "nan block")
+
+
+def test_error_paths(env):
+    torch, binding = env["torch"], env["binding"]
+    prof = binding.Profiler([(0, 100), (200, 50)])
+    with pytest.raises(binding.BaocError) as e:
+        prof.finalize()                                   # no step yet
+    assert e.value.status == binding.ERR_STATE
+    g = torch.zeros(240, device="cuda:0")
+    with pytest.raises(binding.BaocError) as e:
+        prof.step(g)                                      # last block reaches element 250
+    assert e.value.status == binding.ERR_INVALID
+    prof.step(torch.zeros(250, device="cuda:0"))
+    with pytest.raises(binding.BaocError) as e:
+        prof.finalize([(1, 1, 0, 0, 4)])
+    assert e.value.status == binding.ERR_INVALID
+    with pytest.raises(TypeError):
+        prof.step(torch.zeros(250, device="cuda:0", dtype=torch.bfloat16))
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
+    import ctypes as C
+    h = C.c_void_p()
+    arr = binding._block_array([(0, 100000)])
+    p = binding.default_profile_params()
+    assert binding.load_library().baoc_profile_begin(arr, 1, C.byref(p), ws.data_ptr(), 1024, C.byref(h)) == binding.ERR_WORKSPACE
+    assert binding.load_library().baoc_profile_begin(arr, 1, C.byref(p), ws.data_ptr() + 1, 10 ** 9, C.byref(h)) == binding.ERR_WORKSPACE

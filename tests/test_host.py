@@ -1,0 +1,195 @@
+"""CPU-side checks of the product library: exported symbols, layout validation, allocation solver."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2605_04711_amd as B
+from paper_2605_04711_amd import binding
+from synth import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+RNG = np.random.default_rng(99)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = set()
+    for h in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(baoc_\w+)\s*\(", text))
+    assert {"baoc_profile_begin", "baoc_profile_step", "baoc_profile_finalize", "baoc_allocate"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert B.status_string(0) == "ok"
+    for s in range(-7, 0):
+        assert B.status_string(s) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_defaults_are_the_papers():
+    p = binding.default_profile_params()
+    assert (p.beta_m, p.beta_v) == (np.float32(0.9), np.float32(0.999)) and p.eps == 1e-12 and p.quant_block == 256
+    r = binding.default_risk_params()
+    assert r.gamma == 0.1 and r.A_low == np.log(2.0) and r.A_high == np.log(10.0)
+    assert (r.rho_low, r.rho_high, r.eta_low, r.eta_high, r.use_snr_gate) == (0.2, 0.6, 0.0, 2.0, 1)
+
+
+def ws(blocks, **kw):
+    return binding.workspace_bytes(blocks, binding.default_profile_params(**kw))
+
+
+def test_workspace_size_tracks_the_state_bytes():
+    for name in ("tiny", "resnet50", "llama7b"):
+        w = W.make(name)
+        n = ws(w.blocks, grad_dtype=1 if w.grad_dtype == "bf16" else 0)
+        per = 10 if w.grad_dtype == "bf16" else 12
+        assert per * w.numel <= n <= per * w.numel * 1.02 + (1 << 20) + 40_000 * len(w.blocks)
+
+
+def test_layout_validation():
+    def status(blocks, **kw):
+        with pytest.raises(binding.BaocError) as e:
+            ws(blocks, **kw)
+        return e.value.status
+    assert status([(0, 10), (5, 10)]) == binding.ERR_INVALID               # overlap
+    assert status([(0, 0)]) == binding.ERR_INVALID                         # empty block
+    assert status([(0, 12, 3, 5)]) == binding.ERR_INVALID                  # rows*cols != numel
+    assert status([(0, 10)], quant_block=128) == binding.ERR_UNSUPPORTED
+    assert status([(0, 10)], beta_m=1.0) == binding.ERR_INVALID
+    assert status([(0, 10)], grad_dtype=7) == binding.ERR_INVALID
+    assert status([(0, 1 << 33)]) == binding.ERR_UNSUPPORTED
+    assert status([]) == binding.ERR_INVALID
+    assert ws([(20, 10), (0, 20), (100, 7, 7, 1)]) > 0                     # any order, gaps, touching
+
+
+def test_null_arguments_are_rejected():
+    lib = B.load_library()
+    assert lib.baoc_profile_step(None, None, 0, None) == binding.ERR_INVALID
+    assert lib.baoc_profile_end(None) == binding.ERR_INVALID
+    assert lib.baoc_profile_finalize(None, None, 0, None, None, None, None) == binding.ERR_INVALID
+    assert lib.baoc_allocate(None, None, None, 1, 1, 0, 0.0, None, None, None, None, None) == binding.ERR_INVALID
+
+
+# ---------------------------------------------------------------- baoc_allocate against the oracle
+
+def instance(N, K, kind):
+    if kind == "int":
+        risk = RNG.integers(0, 5, (N, K)).astype(np.float64)
+    elif kind == "flat":
+        risk = np.zeros((N, K))
+    else:
+        risk = RNG.random((N, K)) * 3
+    mem = RNG.integers(0, 12, (N, K)).astype(np.int64)
+    tc = RNG.integers(1, 6, (N, K)) * 0.25
+    bm = int(mem.min(1).sum() + RNG.random() * (mem.max(1).sum() - mem.min(1).sum()))
+    bt = float(tc.min(1).sum() + RNG.random() * (tc.max(1).sum() - tc.min(1).sum()))
+    return risk, mem, tc, bm, bt
+
+
+def both(solver, risk, mem, tc, bm, bt, fb=None):
+    ref = solver(risk, mem, tc, bm, bt, fb)
+    try:
+        x, obj, m, t = B.allocate(risk, mem, tc, bm, bt, fb)
+        got = (0, x, obj, m, t)
+    except B.BaocError as e:
+        got = (e.status, None, None, None, None)
+    assert got[0] == ref[0]
+    if ref[0] == 0:
+        assert list(got[1]) == list(ref[1]) and got[2:] == ref[2:]
+    return got
+
+
+@pytest.mark.parametrize("kind", ["real", "int", "flat"])
+def test_allocate_matches_enumeration(kind):
+    for _ in range(60):
+        N, K = int(RNG.integers(1, 9)), int(RNG.integers(1, 5))
+        risk, mem, tc, bm, bt = instance(N, K, kind)
+        fb = (RNG.random((N, K)) < 0.15).astype(np.uint8) if RNG.random() < 0.3 else None
+        both(oracle.allocate_brute, risk, mem, tc, bm, bt, fb)
+
+
+@pytest.mark.parametrize("kind", ["real", "int", "flat"])
+def test_allocate_matches_dynamic_programme_on_larger_instances(kind):
+    for _ in range(12):
+        N, K = int(RNG.integers(20, 60)), int(RNG.integers(3, 8))
+        risk, mem, tc, bm, bt = instance(N, K, kind)
+        both(oracle.allocate_dp, risk, mem, tc, bm, bt)
+
+
+def test_allocate_tiny_workload_instance_by_enumeration():
+    w = W.make("tiny")
+    mem, tc, bm, _ = W.allocation_inputs(w)
+    risk = RNG.random(mem.shape) * 2
+    got = both(oracle.allocate_brute, risk, mem, tc, bm, 1e9)
+    assert got[0] == 0 and got[3] <= bm
+
+
+def test_allocate_slack_budgets_is_rowwise_argmin():
+    risk = RNG.integers(0, 4, (200, 6)).astype(np.float64)
+    mem = RNG.integers(0, 10 ** 9, (200, 6)); tc = RNG.random((200, 6))
+    x, *_ = B.allocate(risk, mem, tc, 2 ** 62, 1e12)
+    assert list(x) == list(np.argmin(risk, axis=1))
+
+
+def test_allocate_errors_and_exclusions():
+    risk = np.array([[0.1, 0.8], [0.3, 0.5]]); mem = np.array([[4, 1], [4, 1]]); tc = np.ones((2, 2))
+    with pytest.raises(B.BaocError) as e:
+        B.allocate(risk, mem, tc, 1, 10.0)
+    assert e.value.status == binding.ERR_INFEASIBLE
+    with pytest.raises(B.BaocError) as e:
+        B.allocate(risk, mem, tc, 8, float("nan"))
+    assert e.value.status == binding.ERR_INVALID
+    with pytest.raises(B.BaocError) as e:
+        B.allocate(risk, -mem, tc, 8, 10.0)
+    assert e.value.status == binding.ERR_INVALID
+    bad = risk.copy(); bad[0, :] = np.inf
+    with pytest.raises(B.BaocError) as e:
+        B.allocate(bad, mem, tc, 8, 10.0)
+    assert e.value.status == binding.ERR_INFEASIBLE          # a block with no allowed pair left
+    x, obj, m, t = B.allocate(risk, mem, tc, 5, 10.0)
+    assert list(x) == [0, 1] and obj == pytest.approx(0.6) and m == 5 and t == 2.0
+    x, *_ = B.allocate(risk, mem, tc, 8, 10.0, forbidden=[[1, 0], [0, 0]])
+    assert list(x) == [1, 0]
+
+
+def test_allocate_node_limit_fails_loudly():
+    risk, mem, tc, bm, bt = instance(40, 6, "real")
+    B.load_library().baoc_allocate_set_node_limit(3)
+    try:
+        with pytest.raises(B.BaocError) as e:
+            B.allocate(risk, mem, tc, bm, bt)
+        assert e.value.status == binding.ERR_LIMIT
+    finally:
+        B.load_library().baoc_allocate_set_node_limit(0)
+
+
+@pytest.mark.parametrize("name", ["resnet50", "unet", "llama7b"])
+def test_allocate_full_size_instances_properties(name):
+    """No enumeration reaches these sizes: check feasibility, the bracket
+    LP-relaxation bound <= optimum <= greedy, and agreement with a library MILP solver."""
+    from scipy.optimize import Bounds, LinearConstraint, milp
+    w = W.make(name)
+    mem, tc, bm, cap = W.allocation_inputs(w)
+    N, K = mem.shape
+    risk = np.round(RNG.random((N, K)) * 2 + np.linspace(0, 1, K)[None, ::-1], 6)
+    cap = 1.3 * N
+    x, obj, m, t = B.allocate(risk, mem, tc, bm, cap)
+    assert m <= bm and t <= cap + 1e-9
+    assert m == sum(mem[i, x[i]] for i in range(N)) and obj == pytest.approx(sum(risk[i, x[i]] for i in range(N)), abs=1e-6)
+    A_one = np.kron(np.eye(N), np.ones((1, K)))
+    cons = [LinearConstraint(A_one, 1, 1), LinearConstraint(mem.reshape(1, -1).astype(float), -np.inf, bm),
+            LinearConstraint(tc.reshape(1, -1), -np.inf, cap)]
+    lp = milp(risk.reshape(-1), constraints=cons, bounds=Bounds(0, 1))                          # relaxation
+    assert lp.success and lp.fun <= obj + 1e-6
+    ip = milp(risk.reshape(-1), constraints=cons, integrality=np.ones(N * K), bounds=Bounds(0, 1),
+              options=dict(mip_rel_gap=0.0, time_limit=60))
+    if ip.success and ip.status == 0:
+        assert obj <= ip.fun + 1e-6 and obj >= ip.fun - 1e-5 * max(1.0, abs(ip.fun))
