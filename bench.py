@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the BAOC gradient-stream profiler on one MI355X.
+
+A "step" of the contract is 1/K of one profiling window: the timed region holds
+baoc_profile_begin, K calls of baoc_profile_step on gradients already resident in
+HBM, baoc_profile_finalize (quantile selection, metrics, risk table) and
+baoc_allocate.  `value` = K * D / (time of that region) in gradient elements per
+second.  The roofline object is about the dominant kernel alone (the fused step
+pass), timed with HIP events on the launch stream inside the same region.
+
+Prints ONE JSON line.  The CPU oracle appears only in the cpu_baseline leg.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+BYTES_PER_ELEM = {"f32": 28, "bf16": 22}   # g read, g_prev read+write, m and v read+write
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="K profile steps in the timed window (0 = the workload's T)")
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--ring", type=int, default=4, help="distinct pre-generated gradient buffers cycled through")
+    ap.add_argument("--chunk-groups", type=int, default=0)
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB -> 1 GiB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "k_step_pmc_traffic.txt"))
+    return ap.parse_args()
+
+
+def read_traffic(path, workload):
+    """`<workload> traffic_bytes_per_launch <N>` lines written from rocprofv3 --pmc runs, or None."""
+    try:
+        for line in open(path):
+            f = line.split("#", 1)[0].split()
+            if len(f) >= 3 and f[0] == workload and f[1] == "traffic_bytes_per_launch":
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, ring, seed, params):
+    """The oracle as it stands, threads over blocks, on a bounded sample of the same workload."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_params, to_host_bits
+    budget = 250_000_000                                  # coordinates in the sample
+    order = sorted(range(len(w.blocks)), key=lambda i: (abs(w.blocks[i].numel - 16_777_216), i))
+    pick, tot = [], 0
+    for i in order:
+        if tot + w.blocks[i].numel <= budget and len(pick) < 16:
+            pick.append(i); tot += w.blocks[i].numel
+    if not pick:
+        pick = [min(range(len(w.blocks)), key=lambda i: w.blocks[i].numel)]; tot = w.blocks[pick[0]].numel
+    steps = 2
+    data = [[to_host_bits(ring[t % len(ring)][w.blocks[i].offset:w.blocks[i].offset + w.blocks[i].numel]) for i in pick]
+            for t in range(steps)]
+    blocks = [oracle.Block(w.blocks[i].numel, **oracle_params(params)) for i in pick]
+    cores = min(16, os.cpu_count() or 1, len(pick))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as pool:
+        for t in range(steps):
+            list(pool.map(lambda k: blocks[k].step(data[t][k]), range(len(pick))))
+        list(pool.map(lambda b: b.finalize(), blocks))
+    dt = time.perf_counter() - t0
+    return {"value": tot * steps / dt, "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(pick)} blocks ({tot:,} coordinates) of {w.name}, {steps} steps + finalize, threads over blocks",
+            "seconds": round(dt, 3)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build profiles on ONE GPU (no sharding or collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2605_04711_amd as B
+    from paper_2605_04711_amd import binding
+    from synth import device, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load_library(); device.lib()
+    dev = torch.device("cuda:0")
+    w = W.make(a.workload, seed=a.seed)
+    K = a.steps or w.T
+    D = w.numel
+    params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=a.chunk_groups)
+    mem, tc, b_mem, cap = W.allocation_inputs(w)
+    cap = 1e12 if not np.isfinite(cap) else cap
+
+    # inputs resident in HBM before the clock starts
+    R = max(1, min(a.ring, K))
+    ring = [device.fill(w, device.new_buffer(w, dev), a.seed, t + 1) for t in range(R)]
+    nbytes = binding.workspace_bytes(w.blocks, params)
+    torch.cuda.synchronize()
+
+    def window(steps, timed):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prof = binding.Profiler(w.blocks, params, device=dev)            # baoc_profile_begin (workspace from torch)
+        t1 = time.perf_counter()
+        for t in range(steps):
+            ev[t][0].record()
+            prof.step(ring[t % R])
+            ev[t][1].record()
+        stats, risk = prof.finalize(w.configs)
+        t2 = time.perf_counter()
+        choice, obj, m_used, t_used = B.allocate(risk, mem, tc, b_mem, cap)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        step_ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+        prof.close()
+        del prof
+        return dict(total=t3 - t0, begin=t1 - t0, steps_and_finalize=t2 - t1, allocate=t3 - t2, step_ms=step_ms,
+                    obj=obj, mem_used=m_used, choice=choice, stats=stats)
+
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if a.warmup > 0:
+        window(a.warmup, False)
+    r = window(K, True)
+    step_ms = r["step_ms"]
+    # t = 1 has no previous gradient but moves the same bytes; all K launches count
+    avg_ms = sum(step_ms) / len(step_ms)
+    bpe = BYTES_PER_ELEM[w.grad_dtype]
+    achieved = bpe * D / (avg_ms * 1e-3) / 1e9
+    finalize_ms = r["steps_and_finalize"] * 1e3 - sum(step_ms)
+    traffic = read_traffic(a.traffic_file, w.name)
+
+    out = {
+        "metric": "gradient elements profiled/sec",
+        "value": K * D / r["total"],
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": K, "warmup": a.warmup,
+        "ms_per_step": r["total"] * 1e3 / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {len(w.blocks)} blocks, {D:,} coordinates, {w.grad_dtype} gradients, "
+                               f"fp32 EMA states, window of {K} steps + finalize + allocate (K={len(w.configs)} configurations)",
+                   "blocks": len(w.blocks), "coordinates": D, "grad_dtype": w.grad_dtype, "window_steps": K,
+                   "gradient_ring": R, "workspace_bytes": nbytes, "chunk_groups": a.chunk_groups or 64},
+        "breakdown_ms": {"begin": round(r["begin"] * 1e3, 3), "step_avg": round(avg_ms, 4),
+                         "step_min": round(min(step_ms), 4), "finalize": round(finalize_ms, 3),
+                         "allocate": round(r["allocate"] * 1e3, 3)},
+        "step_only_elements_per_s": D / (avg_ms * 1e-3),
+        "allocation": {"objective": r["obj"], "state_bytes": int(r["mem_used"]), "budget_bytes": int(b_mem)},
+        "roofline": {"bound": "hbm", "kernel": "k_step", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": bpe * D, "avg_launch_ms": avg_ms},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ring, a.seed, params)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

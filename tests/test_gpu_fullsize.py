@@ -11,17 +11,17 @@ pytestmark = pytest.mark.gpu
 
 
 def sample_blocks(w, small=300_000, n_large=2, frac=0.1, cap=60_000_000, seed=11):
+    """The n_large largest blocks, plus (smallest first, up to `cap` coordinates) every block of at
+    most `small` coordinates and a seeded draw of `frac` of all blocks."""
     rng = np.random.default_rng(seed)
-    order = np.argsort([-b.numel for b in w.blocks])
-    pick = set(int(i) for i in order[:n_large])
-    pick |= {i for i, b in enumerate(w.blocks) if b.numel <= small}
-    for i in rng.permutation(len(w.blocks))[:max(1, int(frac * len(w.blocks)))]:
-        pick.add(int(i))
-    out, total = [], 0
-    for i in sorted(pick, key=lambda i: -w.blocks[i].numel if i in set(int(j) for j in order[:n_large]) else w.blocks[i].numel):
-        if total + w.blocks[i].numel > cap and i not in set(int(j) for j in order[:n_large]):
-            continue
-        out.append(i); total += w.blocks[i].numel
+    order = np.argsort([-b.numel for b in w.blocks], kind="stable")
+    large = [int(i) for i in order[:n_large]]
+    rest = {i for i, b in enumerate(w.blocks) if b.numel <= small}
+    rest |= {int(i) for i in rng.permutation(len(w.blocks))[:max(1, int(frac * len(w.blocks)))]}
+    out, total = list(large), 0
+    for i in sorted(rest - set(large), key=lambda i: (w.blocks[i].numel, i)):
+        if total + w.blocks[i].numel <= cap:
+            out.append(i); total += w.blocks[i].numel
     return sorted(out)
 
 
