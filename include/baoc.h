@@ -117,7 +117,8 @@ int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
 
 /* Validate the layout, carve `d_workspace` (DEVICE, 256-byte aligned, at least
  * workspace_bytes long, owned by the caller and kept alive until
- * baoc_profile_end) and zero the states.  Synchronous on the null stream.
+ * baoc_profile_end) and upload the layout tables.  The states start at zero: the
+ * first step does not read them, it writes them.  Synchronous on the null stream.
  * *out receives the handle.  Errors: INVALID, WORKSPACE, UNSUPPORTED, HIP. */
 int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
                        const baoc_profile_params* params,
@@ -149,7 +150,8 @@ int baoc_profile_finalize(baoc_profiler* p, const baoc_config* configs, uint32_t
 
 /* Device views of one block's state inside the caller's workspace (for
  * checkpoints and bit-level tests): d_m, d_v are fp32[numel]; d_g_prev holds
- * numel elements of the gradient dtype.  Valid until baoc_profile_end. */
+ * numel elements of the gradient dtype.  Pointers are valid until
+ * baoc_profile_end; their contents are defined once the first step has run. */
 int baoc_profile_state(const baoc_profiler* p, uint32_t block,
                        const float** d_m, const float** d_v, const void** d_g_prev);
 

@@ -36,9 +36,11 @@ struct alignas(8) Chunk {
 };
 
 struct alignas(8) BlockRow {
+    uint64_t grad_start;    // the block's offset in the caller's flat gradient buffer
     uint64_t state_start;
     uint64_t numel;
     uint32_t first_chunk, n_chunks;
+    uint32_t groups_per_chunk, pad_;
     uint64_t rank[4];       // order statistics wanted from v: lo(0.1), lo+1, lo(0.9), lo+1
 };
 
@@ -106,20 +108,31 @@ __device__ __forceinline__ float direction(float m, float v, float eps_u)
     return m * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v) + eps_u);
 }
 
+// Every array is touched exactly once per pass: load and store with the nontemporal hint so the
+// stream does not displace anything in L2 / MALL on its way through.
+template <typename T> __device__ __forceinline__ T ld_stream(const void* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+}
+template <typename T> __device__ __forceinline__ void st_stream(void* p, T val)
+{
+    __builtin_nontemporal_store(val, reinterpret_cast<T*>(p));
+}
+
 template <int GT> struct GradIO;
 
 template <> struct GradIO<BAOC_GRAD_F32> {
     typedef float elem;
     __device__ static __forceinline__ void load4(const elem* p, float g[4])
     {
-        f4 t = *reinterpret_cast<const f4*>(p);
+        f4 t = ld_stream<f4>(p);
         g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w;
     }
     __device__ static __forceinline__ float load1(const elem* p) { return *p; }
     __device__ static __forceinline__ void store4(elem* p, const float g[4])
     {
         f4 t = {g[0], g[1], g[2], g[3]};
-        *reinterpret_cast<f4*>(p) = t;
+        st_stream<f4>(p, t);
     }
     static constexpr uintptr_t kAlignMask = 15;
 };
@@ -128,7 +141,7 @@ template <> struct GradIO<BAOC_GRAD_BF16> {
     typedef uint16_t elem;
     __device__ static __forceinline__ void load4(const elem* p, float g[4])
     {
-        u2 t = *reinterpret_cast<const u2*>(p);
+        u2 t = ld_stream<u2>(p);
         g[0] = __builtin_bit_cast(float, t.x << 16); g[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
         g[2] = __builtin_bit_cast(float, t.y << 16); g[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
     }
@@ -139,7 +152,7 @@ template <> struct GradIO<BAOC_GRAD_BF16> {
         u2 t;
         t.x = (__builtin_bit_cast(uint32_t, g[0]) >> 16) | (__builtin_bit_cast(uint32_t, g[1]) & 0xffff0000u);
         t.y = (__builtin_bit_cast(uint32_t, g[2]) >> 16) | (__builtin_bit_cast(uint32_t, g[3]) & 0xffff0000u);
-        *reinterpret_cast<u2*>(p) = t;
+        st_stream<u2>(p, t);
     }
     static constexpr uintptr_t kAlignMask = 7;
 };
@@ -148,7 +161,8 @@ template <> struct GradIO<BAOC_GRAD_BF16> {
 // the fused per-step pass
 // ---------------------------------------------------------------------------
 
-template <int GT>
+// FIRST: the states are known to be zero (first step after begin), so they are not read.
+template <int GT, bool FIRST>
 __global__ __launch_bounds__(256) void k_step(
     const typename GradIO<GT>::elem* __restrict__ grad,
     float* __restrict__ m_all, float* __restrict__ v_all,
@@ -170,13 +184,16 @@ __global__ __launch_bounds__(256) void k_step(
         const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
         const uint64_t si = ck.state_start + e;           // states are padded to whole groups
         float g[4], p[4], m[4], v[4];
-        {
-            f4 t = *reinterpret_cast<const f4*>(m_all + si);
+        if (FIRST) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
+        } else {
+            f4 t = ld_stream<f4>(m_all + si);
             m[0] = t.x; m[1] = t.y; m[2] = t.z; m[3] = t.w;
-            t = *reinterpret_cast<const f4*>(v_all + si);
+            t = ld_stream<f4>(v_all + si);
             v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            IO::load4(gp_all + si, p);
         }
-        IO::load4(gp_all + si, p);
         if (vec_ok && e + 4 <= ck.count) {
             IO::load4(gsrc + e, g);
         } else {                                          // ragged tail or unaligned block start
@@ -194,9 +211,9 @@ __global__ __launch_bounds__(256) void k_step(
         }
         {
             f4 t = {m[0], m[1], m[2], m[3]};
-            *reinterpret_cast<f4*>(m_all + si) = t;
+            st_stream<f4>(m_all + si, t);
             f4 s = {v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<f4*>(v_all + si) = s;
+            st_stream<f4>(v_all + si, s);
         }
         IO::store4(gp_all + si, g);
 
@@ -313,76 +330,146 @@ __global__ __launch_bounds__(256) void k_block_reduce(
 // Digits: bits 30..20, 19..9, 8..0.  Four ranks per block share every pass.
 // ---------------------------------------------------------------------------
 
+// Chunk table from the block rows (one thread per chunk; the owning block by bisection on
+// first_chunk).  A block's groups are split evenly over its chunks, whole groups each.
+__global__ __launch_bounds__(256) void k_build_chunks(const BlockRow* __restrict__ rows, uint32_t n_blocks,
+                                                      Chunk* __restrict__ chunks, uint32_t n_chunks)
+{
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= n_chunks) return;
+    uint32_t lo = 0, hi = n_blocks - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (rows[mid].first_chunk <= c) lo = mid; else hi = mid - 1;
+    }
+    const BlockRow r = rows[lo];
+    const uint64_t g0 = (uint64_t)(c - r.first_chunk) * r.groups_per_chunk;
+    const uint64_t groups = (r.numel + kQB - 1) / kQB;
+    const uint64_t g1 = min(groups, g0 + r.groups_per_chunk);
+    Chunk ck;
+    ck.grad_start = r.grad_start + g0 * kQB;
+    ck.state_start = r.state_start + g0 * kQB;
+    ck.count = (uint32_t)(min(r.numel, g1 * kQB) - g0 * kQB);
+    ck.block = lo;
+    chunks[c] = ck;
+}
+
 __global__ void k_fill_u32(uint32_t* p, uint64_t n, uint32_t val)
 {
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) p[i] = val;
 }
 
 constexpr uint32_t kBins = 2048;
+constexpr uint32_t kHistGrid = 2048;     // persistent workgroups of the histogram passes (8 per CU)
 
+// Each workgroup walks a contiguous run of chunks and keeps the histogram of the parameter block it
+// is in in LDS; the LDS copy is added to the block's global histogram (integer atomics) only when
+// the run crosses into another block and at its end.
 template <int PASS>
 __global__ __launch_bounds__(256) void k_hist(
-    const float* __restrict__ v_all, const Chunk* __restrict__ chunks,
+    const float* __restrict__ v_all, const Chunk* __restrict__ chunks, uint32_t n_chunks,
     const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all)
 {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
     constexpr int NT = PASS == 1 ? 1 : 4;
-    __shared__ uint32_t h[NT * kBins];
-    const Chunk ck = chunks[blockIdx.x];
-    for (uint32_t i = threadIdx.x; i < NT * kBins; i += 256) h[i] = 0;
+    constexpr uint32_t NB = PASS == 3 ? 512 : kBins;
+    __shared__ uint32_t h[NT * NB];
+    const uint32_t per = (n_chunks + gridDim.x - 1) / gridDim.x;
+    const uint32_t c0 = blockIdx.x * per, c1 = min(n_chunks, c0 + per);
+    if (c0 >= c1) return;
+    for (uint32_t i = threadIdx.x; i < NT * NB; i += 256) h[i] = 0;
+    uint32_t cur = chunks[c0].block;
     uint32_t pre[4] = {0, 0, 0, 0};
-    if (PASS > 1) {
+    auto load_prefixes = [&]() {
+        if (PASS > 1) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) pre[t] = sel_prefix[ck.block * 4 + t];
-    }
+            for (int t = 0; t < 4; ++t) pre[t] = sel_prefix[cur * 4 + t];
+        }
+    };
+    auto flush = [&]() {
+        __syncthreads();
+        uint32_t* out = hist_all + (uint64_t)cur * 4 * kBins;
+        for (uint32_t i = threadIdx.x; i < NT * NB; i += 256) {
+            const uint32_t c = h[i];
+            if (c) { atomicAdd(&out[(i / NB) * kBins + (i % NB)], c); h[i] = 0; }
+        }
+        __syncthreads();
+    };
+    load_prefixes();
     __syncthreads();
-    const uint32_t* bits = reinterpret_cast<const uint32_t*>(v_all + ck.state_start);
-    for (uint32_t e = threadIdx.x * 4; e < ck.count; e += 1024) {
-        typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-        const u4 w = *reinterpret_cast<const u4*>(bits + e);        // padded state: always in bounds
-        const uint32_t key[4] = {w.x & 0x7fffffffu, w.y & 0x7fffffffu, w.z & 0x7fffffffu, w.w & 0x7fffffffu};
+    for (uint32_t c = c0; c < c1; ++c) {
+        const Chunk ck = chunks[c];
+        if (ck.block != cur) { flush(); cur = ck.block; load_prefixes(); }
+        const uint32_t* bits = reinterpret_cast<const uint32_t*>(v_all + ck.state_start);
+        for (uint32_t e0 = threadIdx.x * 4; e0 < ck.count; e0 += 4096) {
+            u4 w[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (e + j >= ck.count) break;
-            if (PASS == 1) {
-                atomicAdd(&h[key[j] >> 20], 1u);
-            } else {
-                const uint32_t hi = PASS == 2 ? key[j] >> 20 : key[j] >> 9;
-                const uint32_t bin = PASS == 2 ? (key[j] >> 9) & 0x7ffu : key[j] & 0x1ffu;
+            for (int q = 0; q < 4; ++q)                              // padded state: e < count is in bounds
+                if (e0 + q * 1024 < ck.count) w[q] = ld_stream<u4>(bits + e0 + q * 1024);
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (hi == pre[t]) atomicAdd(&h[t * kBins + bin], 1u);
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t e = e0 + q * 1024;
+                if (e >= ck.count) break;
+                const uint32_t key[4] = {w[q].x & 0x7fffffffu, w[q].y & 0x7fffffffu, w[q].z & 0x7fffffffu, w[q].w & 0x7fffffffu};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (e + j >= ck.count) break;
+                    if (PASS == 1) {
+                        atomicAdd(&h[key[j] >> 20], 1u);
+                    } else {
+                        const uint32_t hi = PASS == 2 ? key[j] >> 20 : key[j] >> 9;
+                        const uint32_t bin = PASS == 2 ? (key[j] >> 9) & 0x7ffu : key[j] & 0x1ffu;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (hi == pre[t]) atomicAdd(&h[t * NB + bin], 1u);
+                    }
+                }
             }
         }
     }
-    __syncthreads();
-    uint32_t* out = hist_all + (uint64_t)ck.block * 4 * kBins;
-    for (uint32_t i = threadIdx.x; i < NT * kBins; i += 256)
-        if (h[i]) atomicAdd(&out[i], h[i]);
+    flush();
 }
 
-// One thread per (block, rank): walk the histogram to the bin that holds the rank,
-// extend the key prefix by that digit and keep the rank inside the bin.
+// One wavefront per (block, rank): every lane sums a run of consecutive bins, a wavefront scan
+// finds the lane whose run holds the rank, and that lane walks its run.  The key prefix grows by
+// the digit found and the rank is made relative to that bin.  Counts fit 32 bits (numel < 2^32).
 template <int PASS>
-__global__ void k_pick(const uint32_t* __restrict__ hist_all, const BlockRow* __restrict__ rows,
-                       uint32_t* __restrict__ sel_prefix, uint64_t* __restrict__ sel_rank,
-                       float* __restrict__ order_stat, uint32_t n_blocks)
+__global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_all, const BlockRow* __restrict__ rows,
+                                             uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ sel_rank,
+                                             float* __restrict__ order_stat)
 {
-    const uint32_t id = blockIdx.x * blockDim.x + threadIdx.x;
-    if (id >= n_blocks * 4) return;
-    const uint32_t b = id >> 2, t = id & 3;
-    const uint32_t* h = hist_all + ((uint64_t)b * 4 + (PASS == 1 ? 0 : t)) * kBins;
-    uint64_t r = PASS == 1 ? rows[b].rank[t] : sel_rank[id];
-    const uint32_t nb = PASS == 3 ? 512 : kBins;
-    uint32_t bin = 0;
-    for (; bin + 1 < nb; ++bin) {
-        const uint32_t c = h[bin];
-        if (r < c) break;
-        r -= c;
+    constexpr uint32_t NB = PASS == 3 ? 512 : kBins, PER = NB / 64;
+    const uint32_t id = blockIdx.x, b = id >> 2, t = id & 3, lane = threadIdx.x;
+    const uint32_t* h = hist_all + ((uint64_t)b * 4 + (PASS == 1 ? 0 : t)) * kBins + lane * PER;
+    const uint32_t r = PASS == 1 ? (uint32_t)rows[b].rank[t] : sel_rank[id];
+    uint32_t cnt[PER], mine = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < PER; ++i) { cnt[i] = h[i]; mine += cnt[i]; }
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d);
+        if ((int)lane >= d) incl += o;
     }
-    const uint32_t prefix = PASS == 1 ? bin : ((sel_prefix[id] << (PASS == 2 ? 11 : 9)) | bin);
-    sel_prefix[id] = prefix;
-    sel_rank[id] = r;
-    if (PASS == 3) order_stat[id] = __builtin_bit_cast(float, prefix);
+    const uint32_t excl = incl - mine;
+    const uint64_t holders = __ballot(r >= excl && r < incl);
+    const uint32_t owner = holders ? (uint32_t)__builtin_ctzll(holders) : 63u;
+    if (lane == owner) {
+        uint32_t rr = r - excl, bin = PER - 1;
+        bool found = false;
+#pragma unroll
+        for (uint32_t i = 0; i < PER; ++i) {
+            if (!found) {
+                if (rr < cnt[i] || i == PER - 1) { bin = i; found = true; }
+                else rr -= cnt[i];
+            }
+        }
+        bin += lane * PER;
+        const uint32_t prefix = PASS == 1 ? bin : ((sel_prefix[id] << (PASS == 2 ? 11 : 9)) | bin);
+        sel_prefix[id] = prefix;
+        sel_rank[id] = rr;
+        if (PASS == 3) order_stat[id] = __builtin_bit_cast(float, prefix);
+    }
 }
 
 }  // namespace baoc
@@ -394,7 +481,7 @@ __global__ void k_pick(const uint32_t* __restrict__ hist_all, const BlockRow* __
 using namespace baoc;
 
 struct Plan {
-    std::vector<Chunk> chunks;
+    uint64_t n_chunks = 0;
     std::vector<BlockRow> rows;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
     uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
@@ -451,7 +538,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
 
     const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : kDefaultChunkGroups;
     Plan& P = *out;
-    P.chunks.clear(); P.rows.resize(n);
+    P.n_chunks = 0; P.rows.resize(n);
     uint64_t state = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const baoc_block& b = blocks[i];
@@ -459,20 +546,11 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         const uint64_t nch = (groups + cg - 1) / cg;
         const uint64_t per = (groups + nch - 1) / nch;               // balanced, whole groups
         BlockRow& r = P.rows[i];
-        r.state_start = state; r.numel = b.numel;
-        r.first_chunk = (uint32_t)P.chunks.size();
-        uint64_t g0 = 0;
-        while (g0 < groups) {
-            const uint64_t g1 = std::min(groups, g0 + per);
-            Chunk c;
-            c.grad_start = b.offset + g0 * kQB;
-            c.state_start = state + g0 * kQB;
-            c.count = (uint32_t)(std::min<uint64_t>(b.numel, g1 * kQB) - g0 * kQB);
-            c.block = i;
-            P.chunks.push_back(c);
-            g0 = g1;
-        }
-        r.n_chunks = (uint32_t)P.chunks.size() - r.first_chunk;
+        r.grad_start = b.offset; r.state_start = state; r.numel = b.numel;
+        r.first_chunk = (uint32_t)P.n_chunks;
+        r.n_chunks = (uint32_t)((groups + per - 1) / per);
+        r.groups_per_chunk = (uint32_t)per; r.pad_ = 0;
+        P.n_chunks += r.n_chunks;
         for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
             const double pos = (q == 0 ? 0.1 : 0.9) * (double)(b.numel - 1);
             const uint64_t lo = (uint64_t)std::floor(pos);
@@ -480,7 +558,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
             r.rank[2 * q + 1] = std::min<uint64_t>(lo + 1, b.numel - 1);
         }
         state += groups * kQB;
-        if (P.chunks.size() > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
+        if (P.n_chunks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
     }
     P.padded = state;
     const uint64_t gsz = prm->grad_dtype == BAOC_GRAD_F32 ? 4 : 2;
@@ -488,13 +566,13 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_m = o;        o = align_up(o + P.padded * 4, 256);
     P.off_v = o;        o = align_up(o + P.padded * 4, 256);
     P.off_gp = o;       o = align_up(o + P.padded * gsz, 256);
-    P.off_partials = o; o = align_up(o + P.chunks.size() * kNumSums * 4, 256);
-    P.off_chunks = o;   o = align_up(o + P.chunks.size() * sizeof(Chunk), 256);
+    P.off_partials = o; o = align_up(o + P.n_chunks * kNumSums * 4, 256);
+    P.off_chunks = o;   o = align_up(o + P.n_chunks * sizeof(Chunk), 256);
     P.off_rows = o;     o = align_up(o + (uint64_t)n * sizeof(BlockRow), 256);
     P.off_rec = o;      o = align_up(o + (uint64_t)n * kRecDoubles * 8, 256);
     P.off_hist = o;     o = align_up(o + (uint64_t)n * 4 * kBins * 4, 256);
     P.off_selp = o;     o = align_up(o + (uint64_t)n * 4 * 4, 256);
-    P.off_selr = o;     o = align_up(o + (uint64_t)n * 4 * 8, 256);
+    P.off_selr = o;     o = align_up(o + (uint64_t)n * 4 * 4, 256);
     P.off_ostat = o;    o = align_up(o + (uint64_t)n * 4 * 4, 256);
     P.total = o;
     return BAOC_OK;
@@ -532,9 +610,16 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     h->blocks.assign(blocks, blocks + n_blocks);
     h->ws = static_cast<char*>(d_workspace);
     const Plan& P = h->plan;
-    hipError_t e = hipMemset(h->ws, 0, P.total);
-    if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_chunks, P.chunks.data(), P.chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+    // The first step treats m, v and g_prev as zero without reading them and writes all of them
+    // (padding included), so only the small tail of the workspace is cleared here.
+    hipError_t e = hipMemset(h->ws + P.off_rec, 0, P.total - P.off_rec);
     if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_rows, P.rows.data(), P.rows.size() * sizeof(BlockRow), hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_build_chunks, dim3((uint32_t)((P.n_chunks + 255) / 256)), dim3(256), 0, nullptr,
+                           reinterpret_cast<const BlockRow*>(h->ws + P.off_rows), n_blocks,
+                           reinterpret_cast<Chunk*>(h->ws + P.off_chunks), (uint32_t)P.n_chunks);
+        e = hipGetLastError();
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { (void)hipGetLastError(); delete h; return BAOC_ERR_HIP; }
     h->h_rec.resize((size_t)n_blocks * kRecDoubles);
@@ -556,13 +641,18 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
     float* v = reinterpret_cast<float*>(h->ws + P.off_v);
     const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
     float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
-    const uint32_t grid = (uint32_t)P.chunks.size();
-    if (q.grad_dtype == BAOC_GRAD_F32)
-        hipLaunchKernelGGL(k_step<BAOC_GRAD_F32>, dim3(grid), dim3(256), 0, st,
-                           static_cast<const float*>(d_grad_flat), m, v, reinterpret_cast<float*>(h->ws + P.off_gp), ch, part, k);
-    else
-        hipLaunchKernelGGL(k_step<BAOC_GRAD_BF16>, dim3(grid), dim3(256), 0, st,
-                           static_cast<const uint16_t*>(d_grad_flat), m, v, reinterpret_cast<uint16_t*>(h->ws + P.off_gp), ch, part, k);
+    const uint32_t grid = (uint32_t)P.n_chunks;
+    typedef float* fp; typedef uint16_t* hp;
+    const bool first = h->steps == 0;
+    if (q.grad_dtype == BAOC_GRAD_F32) {
+        auto kern = first ? k_step<BAOC_GRAD_F32, true> : k_step<BAOC_GRAD_F32, false>;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st,
+                           static_cast<const float*>(d_grad_flat), m, v, reinterpret_cast<fp>(h->ws + P.off_gp), ch, part, k);
+    } else {
+        auto kern = first ? k_step<BAOC_GRAD_BF16, true> : k_step<BAOC_GRAD_BF16, false>;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st,
+                           static_cast<const uint16_t*>(d_grad_flat), m, v, reinterpret_cast<hp>(h->ws + P.off_gp), ch, part, k);
+    }
     h->steps += 1;
     hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(256), 0, st,
                        part, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
@@ -588,28 +678,28 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
     if (!(rp.A_high != rp.A_low) || !(rp.rho_high != rp.rho_low) || !(rp.eta_high != rp.eta_low)) return BAOC_ERR_INVALID;
 
     const Plan& P = h->plan;
-    const uint32_t N = (uint32_t)P.rows.size(), nch = (uint32_t)P.chunks.size();
+    const uint32_t N = (uint32_t)P.rows.size(), nch = (uint32_t)P.n_chunks;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const float* v = reinterpret_cast<const float*>(h->ws + P.off_v);
     const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
     const BlockRow* rows = reinterpret_cast<const BlockRow*>(h->ws + P.off_rows);
     uint32_t* hist = reinterpret_cast<uint32_t*>(h->ws + P.off_hist);
     uint32_t* selp = reinterpret_cast<uint32_t*>(h->ws + P.off_selp);
-    uint64_t* selr = reinterpret_cast<uint64_t*>(h->ws + P.off_selr);
+    uint32_t* selr = reinterpret_cast<uint32_t*>(h->ws + P.off_selr);
     float* ostat = reinterpret_cast<float*>(h->ws + P.off_ostat);
     const uint64_t hist_words = (uint64_t)N * 4 * kBins;
     const uint32_t fill_grid = (uint32_t)std::min<uint64_t>((hist_words + 255) / 256, 4096);
-    const uint32_t pick_grid = (N * 4 + 63) / 64;
+    const uint32_t hist_grid = std::min(nch, kHistGrid);
 
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<1>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
-    hipLaunchKernelGGL(k_pick<1>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+    hipLaunchKernelGGL(k_hist<1>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
+    hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<2>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
-    hipLaunchKernelGGL(k_pick<2>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+    hipLaunchKernelGGL(k_hist<2>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
+    hipLaunchKernelGGL(k_pick<2>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<3>, dim3(nch), dim3(256), 0, st, v, ch, selp, hist);
-    hipLaunchKernelGGL(k_pick<3>, dim3(pick_grid), dim3(64), 0, st, hist, rows, selp, selr, ostat, N);
+    hipLaunchKernelGGL(k_hist<3>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
+    hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
 
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h->h_rec.data(), h->ws + P.off_rec, h->h_rec.size() * 8, hipMemcpyDeviceToHost, st);
