@@ -21,7 +21,6 @@
 #include <cstdint>
 #include <cstring>
 #include <limits>
-#include <map>
 #include <vector>
 
 #include "baoc_internal.h"
@@ -123,6 +122,45 @@ void improve(const Instance& I, Heuristic& H)
     }
 }
 
+// Greedy descent from the unconstrained optimum: start from the least-risk configuration of every
+// block and, while a budget is exceeded, take the swap that buys the most relief per unit of added
+// risk (relief = reduction of the excess over both rows, each in units of its budget).
+void greedy_descent(const Instance& I, Heuristic& H)
+{
+    std::vector<uint32_t> pick(I.N);
+    int64_t W = 0, T = 0;
+    for (uint32_t i = 0; i < I.N; ++i) {
+        uint32_t b = 0;
+        for (uint32_t k = 1; k < I.items[i].size(); ++k)
+            if (I.items[i][k].phi < I.items[i][b].phi) b = k;
+        pick[i] = b; W += I.items[i][b].w; T += I.items[i][b].t;
+    }
+    const double n1 = 1.0 / std::max<double>(1.0, (double)I.B1), n2 = 1.0 / std::max<double>(1.0, (double)I.B2);
+    for (uint64_t guard = 0; (W > I.B1 || T > I.B2) && guard < (uint64_t)I.N * 64; ++guard) {
+        double best = -1.0; uint32_t bi = 0, bk = 0; bool any = false;
+        for (uint32_t i = 0; i < I.N; ++i) {
+            const Item& cur = I.items[i][pick[i]];
+            for (uint32_t k = 0; k < I.items[i].size(); ++k) {
+                const Item& it = I.items[i][k];
+                double relief = 0.0;
+                if (W > I.B1) relief += (double)std::min<int64_t>(cur.w - it.w, W - I.B1) * n1;
+                if (T > I.B2) relief += (double)std::min<int64_t>(cur.t - it.t, T - I.B2) * n2;
+                if (!(relief > 0.0)) continue;
+                const double cost = (double)std::max<int64_t>(it.phi - cur.phi, 0) + 1.0;
+                const double score = relief / cost;
+                if (!any || score > best) { any = true; best = score; bi = i; bk = k; }
+            }
+        }
+        if (!any) return;
+        const Item& cur = I.items[bi][pick[bi]]; const Item& it = I.items[bi][bk];
+        W += it.w - cur.w; T += it.t - cur.t; pick[bi] = bk;
+    }
+    Heuristic G;
+    consider(I, pick, G);
+    improve(I, G);
+    if (G.have && (!H.have || G.Z < H.Z)) H = G;
+}
+
 // Concave maximisation of the dual in one multiplier by bisection on the sign of the subgradient.
 double bisect(const Instance& I, bool first_row, double other, Heuristic& H)
 {
@@ -157,7 +195,7 @@ Multiplier to_integer(double l1, double l2)
     return m;
 }
 
-struct State { int64_t Z, W, T; uint32_t node; };    // node: index into the arena (parent, cfg)
+struct State { int64_t Z, W, T; uint32_t node; float slack; };   // node: arena index (parent, cfg); slack: cutoff - bound, scaled
 struct Node { uint32_t parent; uint32_t item; };
 
 struct Key { int64_t Z; uint32_t seq; };
@@ -186,6 +224,7 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
         if (same) break;
     }
     improve(I, H);
+    greedy_descent(I, H);
 
     std::vector<Multiplier> mult;
     mult.push_back(to_integer(l1, l2));
@@ -206,73 +245,129 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
             sufRC[m][i] = sufRC[m][i + 1] + best;
         }
     }
-    const bool have_cut = H.have;
-    const int64_t cutoff = H.have ? H.Z : 0;
+    // double images of the multipliers: a bound far from the cutoff is decided in floating point,
+    // only a near miss is evaluated exactly
+    std::vector<double> Sd(M), L1d(M), L2d(M);
+    std::vector<std::vector<double>> sufRCd(M, std::vector<double>(N + 1));
+    for (size_t m = 0; m < M; ++m) {
+        Sd[m] = (double)mult[m].S; L1d[m] = (double)mult[m].L1; L2d[m] = (double)mult[m].L2;
+        for (uint32_t i = 0; i <= N; ++i) sufRCd[m][i] = (double)sufRC[m][i];
+    }
+    int64_t z_max = 0;                                 // no assignment costs more than this
+    for (uint32_t i = 0; i < N; ++i) {
+        int64_t mx = I.items[i][0].phi;
+        for (const Item& it : I.items[i]) mx = std::max(mx, it.phi);
+        z_max += mx;
+    }
+    const int64_t ub = H.have ? H.Z : z_max;
 
     const uint64_t limit = g_node_limit ? g_node_limit : kDefaultNodeLimit;
     std::vector<Node> arena;
-    arena.reserve(1 << 16);
-    arena.push_back({0xffffffffu, 0});
-    std::vector<State> cur{{0, 0, 0, 0}}, nxt;
+    std::vector<State> cur, nxt;
     std::vector<uint32_t> order;
     std::vector<uint8_t> dead;
+    std::vector<std::pair<int64_t, Key>> stair;        // (T, best key among kept states with time <= T), T ascending
 
-    for (uint32_t i = 0; i < N; ++i) {
-        nxt.clear();
-        for (const State& s : cur) {
-            for (uint32_t k = 0; k < I.items[i].size(); ++k) {
-                const Item& it = I.items[i][k];
-                State c{s.Z + it.phi, s.W + it.w, s.T + it.t, 0};
-                if (c.W + sufW[i + 1] > I.B1 || c.T + sufT[i + 1] > I.B2) continue;
-                if (have_cut) {
+    // run(cutoff, level_cap): build the state lists for this cutoff.  A run that ends with states
+    // has kept every prefix of every assignment of value <= cutoff that is not dominated.
+    enum { kRunOk = 0, kRunEmpty = 1, kRunCapped = 2, kRunLimit = 3 };
+    std::vector<float> slacks;
+    auto run = [&](int64_t cutoff, size_t level_cap, size_t beam) -> int {
+        arena.clear();
+        arena.push_back({0xffffffffu, 0});
+        cur.assign(1, State{0, 0, 0, 0, 0.f});
+        bool empty = false;
+        for (uint32_t i = 0; i < N && !empty; ++i) {
+            nxt.clear();
+            for (const State& s : cur) {
+                for (uint32_t k = 0; k < I.items[i].size(); ++k) {
+                    const Item& it = I.items[i][k];
+                    State c{s.Z + it.phi, s.W + it.w, s.T + it.t, 0, 0.f};
+                    if (c.W + sufW[i + 1] > I.B1 || c.T + sufT[i + 1] > I.B2) continue;
                     bool cut = false;
                     for (size_t m = 0; m < M && !cut; ++m) {
+                        const double a = (double)c.Z * Sd[m], b = L1d[m] * (double)c.W, d = L2d[m] * (double)c.T;
+                        const double lhs_d = a + b + d + sufRCd[m][i + 1], rhs_d = (double)cutoff * Sd[m];
+                        if (m == 0) c.slack = (float)((rhs_d - lhs_d) / Sd[0]);
+                        const double tol = 1e-9 * (std::fabs(a) + b + std::fabs(d) + std::fabs(sufRCd[m][i + 1]) + std::fabs(rhs_d));
+                        if (lhs_d > rhs_d + tol) { cut = true; break; }
+                        if (lhs_d < rhs_d - tol) continue;
                         const i128 lhs = (i128)c.Z * mult[m].S + mult[m].L1 * (i128)c.W + mult[m].L2 * (i128)c.T + sufRC[m][i + 1];
                         cut = lhs > (i128)cutoff * mult[m].S;
                     }
                     if (cut) continue;
+                    if (arena.size() >= limit || arena.size() >= 0xfffffff0ull) return kRunLimit;
+                    c.node = (uint32_t)arena.size();
+                    arena.push_back({s.node, k});
+                    nxt.push_back(c);
                 }
-                if (arena.size() >= limit || arena.size() >= 0xfffffff0ull) return BAOC_ERR_LIMIT;
-                c.node = (uint32_t)arena.size();
-                arena.push_back({s.node, k});
-                nxt.push_back(c);
             }
-        }
-        if (nxt.empty()) return BAOC_ERR_INFEASIBLE;
-        // dominance: sweep by (W, T, key); staircase over T of the best key seen
-        const size_t n = nxt.size();
-        if (n > 1) {
-            order.resize(n);
-            for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
-            std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-                const State &x = nxt[a], &y = nxt[b];
-                if (x.W != y.W) return x.W < y.W;
-                if (x.T != y.T) return x.T < y.T;
-                if (x.Z != y.Z) return x.Z < y.Z;
-                return a < b;
-            });
-            dead.assign(n, 0);
-            std::map<int64_t, Key> stair;             // T -> best key among kept states with time <= T
-            for (uint32_t j : order) {
-                const State& s = nxt[j];
-                const Key key{s.Z, j};
-                auto it = stair.upper_bound(s.T);
-                if (it != stair.begin()) {
-                    auto pv = std::prev(it);
-                    if (pv->second < key) { dead[j] = 1; continue; }
+            if (nxt.empty()) { empty = true; break; }
+            // dominance: sweep by (W, T, key); staircase over T of the best key seen
+            const size_t n = nxt.size();
+            if (n > 1) {
+                order.resize(n);
+                for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
+                std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+                    const State &x = nxt[a], &y = nxt[b];
+                    if (x.W != y.W) return x.W < y.W;
+                    if (x.T != y.T) return x.T < y.T;
+                    if (x.Z != y.Z) return x.Z < y.Z;
+                    return a < b;
+                });
+                dead.assign(n, 0);
+                stair.clear();
+                for (uint32_t j : order) {
+                    const State& s = nxt[j];
+                    const Key key{s.Z, j};
+                    // first entry with T > s.T; the one before it holds the best key with time <= s.T
+                    auto it = std::upper_bound(stair.begin(), stair.end(), s.T,
+                                               [](int64_t t, const std::pair<int64_t, Key>& e) { return t < e.first; });
+                    if (it != stair.begin() && std::prev(it)->second < key) { dead[j] = 1; continue; }
+                    if (it != stair.begin() && std::prev(it)->first == s.T) {
+                        --it;
+                        it->second = key;
+                    } else {
+                        it = stair.insert(it, std::make_pair(s.T, key));
+                    }
+                    auto nx = std::next(it), e = nx;
+                    while (e != stair.end() && !(e->second < key)) ++e;   // entries to the right that are no better
+                    stair.erase(nx, e);
                 }
-                // insert and drop entries to the right that are no better
-                auto ins = stair.insert_or_assign(s.T, key).first;
-                auto nx = std::next(ins);
-                while (nx != stair.end() && !(nx->second < key)) nx = stair.erase(nx);
+                size_t o = 0;
+                for (size_t j = 0; j < n; ++j)
+                    if (!dead[j]) nxt[o++] = nxt[j];
+                nxt.resize(o);
             }
-            size_t o = 0;
-            for (size_t j = 0; j < n; ++j)
-                if (!dead[j]) nxt[o++] = nxt[j];
-            nxt.resize(o);
+            if (beam && nxt.size() > beam) {              // heuristic mode: keep the most promising states
+                slacks.resize(nxt.size());
+                for (size_t j = 0; j < nxt.size(); ++j) slacks[j] = nxt[j].slack;
+                std::nth_element(slacks.begin(), slacks.begin() + (nxt.size() - beam), slacks.end());
+                const float thr = slacks[nxt.size() - beam];
+                size_t o = 0;
+                for (size_t j = 0; j < nxt.size() && o < beam; ++j)
+                    if (nxt[j].slack >= thr) nxt[o++] = nxt[j];
+                nxt.resize(o);
+            }
+            cur.swap(nxt);
+            if (cur.size() > level_cap) return kRunCapped;
         }
-        cur.swap(nxt);
+        return empty ? kRunEmpty : kRunOk;
+    };
+    // First try the incumbent itself as cutoff: the heuristics usually land within 1e-4 of the
+    // optimum and then one pass is all there is.  If the lists grow large the incumbent was poor:
+    // a beam-limited pass of the same recursion finds a better one, then the exact pass is repeated.
+    const size_t no_cap = std::numeric_limits<size_t>::max();
+    int64_t cut = ub;
+    int rc = run(cut, 20000, 0);
+    if (rc == kRunCapped) {
+        rc = run(cut, no_cap, 1024);
+        if (rc == kRunOk)
+            for (const State& st : cur) cut = std::min(cut, st.Z);
+        rc = run(cut, no_cap, 0);
     }
+    if (rc == kRunLimit) return BAOC_ERR_LIMIT;
+    if (rc == kRunEmpty) return BAOC_ERR_INFEASIBLE;
     // best final state: least Z, then earliest in lexicographic order
     size_t best = 0;
     for (size_t j = 1; j < cur.size(); ++j)
