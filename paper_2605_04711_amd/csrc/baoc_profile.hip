@@ -93,13 +93,16 @@ __device__ __forceinline__ float wave_sum(float x)
 
 __device__ __forceinline__ float bf16_widen(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
 
-// round-to-nearest-even of a binary32 to the bf16 grid, result widened back
-__device__ __forceinline__ float bf16_round(float x)
+// Round-to-nearest-even of two binary32 values to the bf16 grid, widened back.  One
+// v_cvt_pk_bf16_f32 (gfx950) converts both; the halves are then moved back to the top of a word.
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void bf16_round2(float a, float b, float& ra, float& rb)
 {
-    uint32_t u = __builtin_bit_cast(uint32_t, x);
-    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
-    uint32_t n = (u | 0x00400000u) & 0xffff0000u;
-    return __builtin_bit_cast(float, (u & 0x7fffffffu) > 0x7f800000u ? n : r);
+    const f2 x = {a, b};
+    const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf2));
+    ra = __builtin_bit_cast(float, w << 16);
+    rb = __builtin_bit_cast(float, w & 0xffff0000u);
 }
 
 // u = m / (sqrt(v) + eps_u) with the hardware's 1-ulp square root and reciprocal
@@ -238,7 +241,8 @@ __global__ __launch_bounds__(256) void k_step(
             const float u32 = direction(mj, vj, k.eps_u);
             acc[U0] = __builtin_fmaf(u32, u32, acc[U0]);
             {   // bf16 round trip
-                const float mb = bf16_round(mj), vb = bf16_round(vj);
+                float mb, vb;
+                bf16_round2(mj, vj, mb, vb);
                 const float ub = direction(mb, vb, k.eps_u);
                 const float du = ub - u32, dm = mb - mj, dv = vb - vj;
                 acc[U1_16] = __builtin_fmaf(u32, ub, acc[U1_16]);
