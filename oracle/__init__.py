@@ -33,7 +33,7 @@ class Stats(C.Structure):
             "Q16", "Q8", "lQ32", "lQ16", "lQ8",
             "err_m16", "err_v16", "err_m8", "err_v8",
             "s_A", "s_rho", "s_snr", "s_M", "C_tilde", "s_F",
-            "m_sq", "v_l1", "g_sq_last")]
+            "m_sq", "v_l1", "g_sq_last", "C", "F")]
 
     def asdict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -74,6 +74,10 @@ def lib():
         L.orc_block_step_f32.argtypes = [vp, vp]
         L.orc_block_step_bf16.argtypes = [vp, vp]
         L.orc_block_finalize.argtypes = [vp, C.POINTER(RiskParams), f64, f64, C.POINTER(Stats)]
+        L.orc_block_structure_residual.restype = f64
+        L.orc_block_structure_residual.argtypes = [vp, u32, u32]
+        L.orc_block_distortion.restype = f64
+        L.orc_block_distortion.argtypes = [vp, vp]
         L.orc_bf16_round.restype = f32
         L.orc_bf16_round.argtypes = [f32]
         L.orc_q8_code.restype = f32
@@ -138,6 +142,19 @@ class Block:
     @property
     def p(self):
         return self._arr(lib().orc_block_p)
+
+    def structure_residual(self, rows, cols):
+        """Eq. 7 on v-hat viewed as rows x cols; 0 for non-matrix blocks."""
+        return lib().orc_block_structure_residual(self._h, int(rows), int(cols))
+
+    def distortion(self, theta):
+        """Eq. 6 with the block's parameters theta (float32, or uint16 bf16 bits)."""
+        theta = np.ascontiguousarray(theta)
+        if theta.dtype == np.uint16:
+            theta = (theta.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        theta = np.ascontiguousarray(theta, dtype=np.float32)
+        assert theta.size == self.numel
+        return lib().orc_block_distortion(self._h, theta.ctypes.data)
 
     def finalize(self, rp=None, C_raw=0.0, F_raw=0.0):
         rp = rp or default_risk_params()

@@ -219,6 +219,7 @@ typedef struct {
     double err_m16, err_v16, err_m8, err_v8;
     double s_A, s_rho, s_snr, s_M, C_tilde, s_F;
     double m_sq, v_l1, g_sq_last;
+    double C, F;                  /* raw Eq. 6 / Eq. 7 values that produced C_tilde and s_F */
 } orc_stats;
 
 typedef struct {
@@ -254,6 +255,54 @@ double orc_quantile(const float *x, uint64_t d, double q)
     double r = quantile_sorted(s, d, q);
     free(s);
     return r;
+}
+
+/* Eq. 7: structure residual of a matrix block.  S = EMA(G*G) is the second moment v-hat
+   viewed as a rows x cols matrix (row-major).  S~ is the rank-1 matrix built from the
+   row means r, the column means c and the grand mean mu: S~_ij = r_i c_j / mu
+   (S~ = 0 when mu = 0).  F = |S - S~|_F / (|S|_F + eps).  Blocks that are not matrices
+   have nothing to factor: F = 0. */
+double orc_block_structure_residual(const orc_block *b, uint32_t rows, uint32_t cols)
+{
+    if (rows == 0 || cols == 0 || (uint64_t)rows * cols != b->d) return 0.0;
+    double *r = (double *)calloc(rows, sizeof(double)), *c = (double *)calloc(cols, sizeof(double));
+    double mu = 0.0;
+    for (uint32_t i = 0; i < rows; ++i)
+        for (uint32_t j = 0; j < cols; ++j) {
+            double s = b->v[(uint64_t)i * cols + j];
+            r[i] += s; c[j] += s; mu += s;
+        }
+    for (uint32_t i = 0; i < rows; ++i) r[i] /= (double)cols;
+    for (uint32_t j = 0; j < cols; ++j) c[j] /= (double)rows;
+    mu /= (double)rows * (double)cols;
+    double num = 0.0, den = 0.0;
+    for (uint32_t i = 0; i < rows; ++i)
+        for (uint32_t j = 0; j < cols; ++j) {
+            double s = b->v[(uint64_t)i * cols + j];
+            double st = mu != 0.0 ? r[i] * c[j] / mu : 0.0;
+            num += (s - st) * (s - st);
+            den += s * s;
+        }
+    free(r); free(c);
+    return sqrt(num) / (sqrt(den) + b->eps);
+}
+
+/* Eq. 6: distortion of the weight-decay direction by the preconditioner
+   p = 1 / (sqrt(v-hat) + eps), p-bar its mean over the block:
+   C = |(p / p-bar - 1) * theta| / (|theta| + eps).  theta: the block's parameters. */
+double orc_block_distortion(const orc_block *b, const float *theta)
+{
+    double pbar = 0.0;
+    for (uint64_t j = 0; j < b->d; ++j) pbar += 1.0 / (sqrt((double)b->v[j]) + b->eps);
+    pbar /= (double)b->d;
+    double num = 0.0, den = 0.0;
+    for (uint64_t j = 0; j < b->d; ++j) {
+        double p = 1.0 / (sqrt((double)b->v[j]) + b->eps);
+        double t = theta[j];
+        double x = (p / pbar - 1.0) * t;
+        num += x * x; den += t * t;
+    }
+    return sqrt(num) / (sqrt(den) + b->eps);
 }
 
 static double clip(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
@@ -311,6 +360,7 @@ int orc_block_finalize(const orc_block *b, const orc_risk_params *rp, double C_r
     o->s_rho = clip((o->rho_bar - rp->rho_low) / (rp->rho_high - rp->rho_low), 0.0, 1.0);
     o->s_snr = clip((log(1.0 + o->snr) - rp->eta_low) / (rp->eta_high - rp->eta_low), 0.0, 1.0);
     o->s_M   = rp->use_snr_gate ? o->s_rho * o->s_snr : o->s_rho;
+    o->C = C_raw; o->F = F_raw;
     o->C_tilde = log(1.0 + C_raw);
     o->s_F   = clip(F_raw, 0.0, 1.0);
     return 0;
