@@ -3,8 +3,8 @@
 
 A "step" of the contract is 1/K of one profiling window: the timed region holds
 baoc_profile_begin, K calls of baoc_profile_step on gradients already resident in
-HBM, baoc_profile_finalize (quantile selection, metrics, risk table) and
-baoc_allocate.  `value` = K * D / (time of that region) in gradient elements per
+HBM, baoc_profile_finalize (quantile selection, structure residual, distortion
+against a resident parameter buffer, metrics, risk table) and baoc_allocate.  `value` = K * D / (time of that region) in gradient elements per
 second.  The roofline object is about the dominant kernel alone (the fused step
 pass), timed with HIP events on the launch stream inside the same region.
 
@@ -109,6 +109,12 @@ def main():
     R = max(1, min(a.ring, K))
     ring = [device.fill(w, device.new_buffer(w, dev), a.seed, t + 1) for t in range(R)]
     nbytes = binding.workspace_bytes(w.blocks, params)
+    # parameters theta for the distortion metric (Eq. 6), same layout and dtype as the gradients
+    gen = torch.Generator(device=dev); gen.manual_seed(a.seed)
+    theta = torch.empty(w.buffer_numel, dtype=ring[0].dtype, device=dev)
+    for lo in range(0, w.buffer_numel, 1 << 28):               # in slices: keeps the fp32 temporary small
+        n = min(1 << 28, w.buffer_numel - lo)
+        theta[lo:lo + n] = (0.02 * torch.randn(n, device=dev, generator=gen)).to(theta.dtype)
     torch.cuda.synchronize()
 
     def window(steps, timed):
@@ -121,7 +127,7 @@ def main():
             ev[t][0].record()
             prof.step(ring[t % R])
             ev[t][1].record()
-        stats, risk = prof.finalize(w.configs)
+        stats, risk = prof.finalize(w.configs, theta=theta)
         t2 = time.perf_counter()
         choice, obj, m_used, t_used = B.allocate(risk, mem, tc, b_mem, cap)
         torch.cuda.synchronize()

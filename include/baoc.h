@@ -80,8 +80,15 @@ typedef struct {
     int32_t use_snr_gate;         /* 1: s_M = s_rho * s_snr (Eq. 17); 0: s_M = s_rho     */
     double lambda_pref;           /* soft preference strength, Sec. 3.2       (0)        */
     const uint8_t* pref_mask;     /* n_configs flags marking C_pref, or NULL             */
-    const double*  C_raw;         /* n_blocks raw distortions C_i (Eq. 6), or NULL = 0   */
-    const double*  F_raw;         /* n_blocks raw structure residuals F_i (Eq. 7), or NULL = 0 */
+    const double*  C_raw;         /* n_blocks raw distortions C_i (Eq. 6) supplied by the caller, or NULL */
+    const double*  F_raw;         /* n_blocks raw structure residuals F_i (Eq. 7) supplied by the caller, or NULL */
+    int32_t compute_F;            /* F_raw == NULL: 1 = compute F from v-hat for matrix blocks
+                                     (rows*cols == numel; other blocks get 0), 0 = F = 0   (1)   */
+    const void* d_theta_flat;     /* C_raw == NULL: DEVICE buffer of the parameters theta, laid out
+                                     like the gradient buffer; C is then computed from it (Eq. 6).
+                                     NULL = C = 0                                                */
+    uint64_t theta_numel;         /* elements in d_theta_flat (must cover every block)           */
+    uint32_t theta_dtype;         /* BAOC_GRAD_F32 | BAOC_GRAD_BF16                              */
 } baoc_risk_params;
 
 /* Per-block result of baoc_profile_finalize: raw metrics of Sec. 3.3 after the
@@ -99,6 +106,7 @@ typedef struct {
     double err_m16, err_v16, err_m8, err_v8;  /* |x^b - x|_2 / (|x|_2 + eps), x = m, v   */
     double s_A, s_rho, s_snr, s_M, C_tilde, s_F;   /* App. A signals                      */
     double m_sq, v_l1, g_sq_last; /* |m|^2, |v|_1, |g_T|^2                                */
+    double C, F;                  /* raw distortion (Eq. 6) and structure residual (Eq. 7) behind C_tilde, s_F */
 } baoc_block_stats;
 
 typedef struct baoc_profiler baoc_profiler;
@@ -140,9 +148,13 @@ int baoc_profile_step(baoc_profiler* p, const void* d_grad_flat, uint64_t grad_n
  * then fills out_stats (HOST, n_blocks entries, in the order given at begin)
  * and out_risk (HOST, n_blocks x n_configs row-major,
  * Phi[i][c] = R_i(c) - lambda_pref [c in C_pref] + gamma Agg(c)).
+ * The structure residual F (Eq. 7: v-hat of a matrix block against the rank-1
+ * matrix of its row and column means) and, when risk_params->d_theta_flat is
+ * given, the distortion C (Eq. 6) are computed on the device in the same call.
  * Either output may be NULL.  The state is kept: more steps may follow and
  * finalize may be called again with other configurations.
- * Errors: INVALID (bits not in {8,16,32}, null configs with out_risk), STATE
+ * Errors: INVALID (bits not in {8,16,32}, null configs with out_risk, theta
+ * buffer shorter than the layout), STATE
  * (no step yet), HIP. */
 int baoc_profile_finalize(baoc_profiler* p, const baoc_config* configs, uint32_t n_configs,
                           const baoc_risk_params* risk_params,

@@ -34,7 +34,9 @@ class RiskParams(C.Structure):
     _fields_ = [("gamma", C.c_double), ("A_low", C.c_double), ("A_high", C.c_double),
                 ("rho_low", C.c_double), ("rho_high", C.c_double), ("eta_low", C.c_double), ("eta_high", C.c_double),
                 ("use_snr_gate", C.c_int32), ("lambda_pref", C.c_double),
-                ("pref_mask", C.c_void_p), ("C_raw", C.c_void_p), ("F_raw", C.c_void_p)]
+                ("pref_mask", C.c_void_p), ("C_raw", C.c_void_p), ("F_raw", C.c_void_p),
+                ("compute_F", C.c_int32), ("d_theta_flat", C.c_void_p), ("theta_numel", C.c_uint64),
+                ("theta_dtype", C.c_uint32)]
 
 
 class BlockStats(C.Structure):
@@ -42,7 +44,7 @@ class BlockStats(C.Structure):
         (n, C.c_double) for n in (
             "rho_bar", "cos_last", "snr", "A", "q10", "q90", "Q16", "Q8", "lQ32", "lQ16", "lQ8",
             "err_m16", "err_v16", "err_m8", "err_v8", "s_A", "s_rho", "s_snr", "s_M", "C_tilde", "s_F",
-            "m_sq", "v_l1", "g_sq_last")]
+            "m_sq", "v_l1", "g_sq_last", "C", "F")]
 
     def asdict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -178,11 +180,24 @@ class Profiler:
     def step_raw(self, d_ptr, numel, stream_handle):
         return self.lib.baoc_profile_step(self._h, d_ptr, numel, stream_handle)
 
-    def finalize(self, configs=None, risk_params=None, pref_mask=None, C_raw=None, F_raw=None, stream=None):
-        """-> (stats: ctypes array of BlockStats, risk: float64 [N, K] or None)."""
+    def finalize(self, configs=None, risk_params=None, pref_mask=None, C_raw=None, F_raw=None, theta=None,
+                 compute_F=None, stream=None):
+        """-> (stats: ctypes array of BlockStats, risk: float64 [N, K] or None).
+
+        theta: flat device tensor of the parameters (float32 or bfloat16, laid out like the gradient
+        buffer); when given the distortion C is computed from it.  F is computed for matrix blocks
+        unless F_raw is given or compute_F is False."""
         torch = self._torch
         rp = risk_params or default_risk_params()
         keep = []
+        if compute_F is not None:
+            rp.compute_F = int(bool(compute_F))
+        if theta is not None:
+            if theta.dtype not in (torch.float32, torch.bfloat16) or not theta.is_contiguous() or theta.device != self.device:
+                raise TypeError(f"theta must be a contiguous float32 or bfloat16 tensor on {self.device}")
+            keep.append(theta)
+            rp.d_theta_flat = theta.data_ptr(); rp.theta_numel = theta.numel()
+            rp.theta_dtype = GRAD_F32 if theta.dtype == torch.float32 else GRAD_BF16
         if pref_mask is not None:
             a = np.ascontiguousarray(pref_mask, dtype=np.uint8); keep.append(a); rp.pref_mask = a.ctypes.data
         if C_raw is not None:

@@ -20,7 +20,8 @@ enum Sum : int {
 
 // per-block record kept on the device, doubles
 enum Rec : int {
-    R_SPP = 16, R_RHO, R_COS, R_NCOS, R_STEPS, R_Q0, R_Q1, R_Q2, R_Q3, kRecDoubles = 32
+    R_SPP = 16, R_RHO, R_COS, R_NCOS, R_STEPS, R_Q0, R_Q1, R_Q2, R_Q3,
+    R_PSUM, R_CNUM, R_CDEN, R_FRES, R_FS2, kRecDoubles = 32
 };
 
 // Raw per-block numbers handed from the device path to the host-side metrics.

@@ -476,6 +476,283 @@ __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_a
     }
 }
 
+// ---------------------------------------------------------------------------
+// Eq. 7: structure residual F of a matrix block.  S = v viewed as rows x cols.
+// A task is a tile of up to 256 rows x 256 columns owned by one wavefront: each
+// lane keeps 4 column sums, each row's sum is a DPP reduction.  Pass A gives row
+// and column partial sums, a per-block finish turns them into the means r, c
+// and mu (fp64), pass B accumulates |S - r c^T / mu|^2 and |S|^2 per task.
+// ---------------------------------------------------------------------------
+
+constexpr uint32_t kTileRows = 256, kTileCols = 256;
+
+struct alignas(8) MatRow {
+    uint64_t state_start;                 // first coordinate of the block in v
+    uint64_t off_r, off_c;                // into the r / c vectors (floats)
+    uint64_t off_rowpart, off_colpart;    // into the partial-sum arrays (floats)
+    uint32_t rows, cols, n_tiles, n_segs;
+    uint32_t first_task, block;
+};
+
+struct MatTask { uint32_t mat, row0, row1, col0, ncols, tile, seg; bool vec; };
+
+__device__ __forceinline__ MatTask decode_task(const MatRow* __restrict__ mats, uint32_t n_mats, uint32_t task)
+{
+    uint32_t lo = 0, hi = n_mats - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (mats[mid].first_task <= task) lo = mid; else hi = mid - 1;
+    }
+    const MatRow& m = mats[lo];
+    const uint32_t local = task - m.first_task;
+    MatTask t;
+    t.mat = lo; t.seg = local / m.n_tiles; t.tile = local % m.n_tiles;
+    t.row0 = t.seg * kTileRows; t.row1 = min(m.rows, t.row0 + kTileRows);
+    t.col0 = t.tile * kTileCols; t.ncols = min(kTileCols, m.cols - t.col0);
+    t.vec = (m.cols & 3u) == 0;           // rows start 16-byte aligned (blocks start on 1 KB)
+    return t;
+}
+
+// Column owned by slot k of a lane: 4 consecutive columns on the vector path, stride 64 otherwise.
+__device__ __forceinline__ uint32_t tile_col(bool vec, uint32_t lane, int k) { return vec ? 4 * lane + k : lane + 64 * k; }
+
+__device__ __forceinline__ void load_tile_row(const float* __restrict__ row, bool vec, uint32_t lane, uint32_t ncols, float x[4])
+{
+    if (vec) {
+        if (4 * lane < ncols) {
+            const f4 t = ld_stream<f4>(row + 4 * lane);
+            x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+        } else {
+            x[0] = x[1] = x[2] = x[3] = 0.f;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = (lane + 64 * k < ncols) ? row[lane + 64 * k] : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_rowcol(const float* __restrict__ v_all, const MatRow* __restrict__ mats,
+                                                uint32_t n_mats, uint32_t n_tasks,
+                                                float* __restrict__ rowpart, float* __restrict__ colpart)
+{
+    const uint32_t lane = threadIdx.x & 63u, task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (task >= n_tasks) return;
+    const MatTask t = decode_task(mats, n_mats, task);
+    const MatRow& m = mats[t.mat];
+    const float* row = v_all + m.state_start + (uint64_t)t.row0 * m.cols + t.col0;
+    float cs[4] = {0.f, 0.f, 0.f, 0.f};
+    float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
+    uint32_t r = t.row0;
+    for (; r + 4 <= t.row1; r += 4) {                       // four rows in flight
+        float x[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) cs[k] += x[q][k];
+            const float rs = wave_sum((x[q][0] + x[q][1]) + (x[q][2] + x[q][3]));
+            if (lane == 0) rp[(uint64_t)q * m.n_tiles] = rs;
+        }
+        row += (uint64_t)4 * m.cols; rp += (uint64_t)4 * m.n_tiles;
+    }
+    for (; r < t.row1; ++r) {
+        float x[4];
+        load_tile_row(row, t.vec, lane, t.ncols, x);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) cs[k] += x[k];
+        const float rs = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
+        if (lane == 0) *rp = rs;
+        row += m.cols; rp += m.n_tiles;
+    }
+    float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t c = tile_col(t.vec, lane, k);
+        if (c < t.ncols) cp[c] = cs[k];
+    }
+}
+
+// r_i, c_j (fp32 for pass B) and mu (fp64) of one matrix block from the partial sums.
+__global__ __launch_bounds__(256) void k_rowcol_finish(const MatRow* __restrict__ mats, const float* __restrict__ rowpart,
+                                                       const float* __restrict__ colpart, float* __restrict__ rvec,
+                                                       float* __restrict__ cvec, double* __restrict__ mu_out)
+{
+    const MatRow m = mats[blockIdx.x];
+    double local = 0.0;
+    for (uint32_t i = threadIdx.x; i < m.rows; i += 256) {
+        const float* rp = rowpart + m.off_rowpart + (uint64_t)i * m.n_tiles;
+        double s = 0.0;
+        for (uint32_t t = 0; t < m.n_tiles; ++t) s += (double)rp[t];
+        const double r = s / (double)m.cols;
+        rvec[m.off_r + i] = (float)r;
+        local += r;
+    }
+    for (uint32_t j = threadIdx.x; j < m.cols; j += 256) {
+        const float* cp = colpart + m.off_colpart + j;
+        double s = 0.0;
+        for (uint32_t g = 0; g < m.n_segs; ++g) s += (double)cp[(uint64_t)g * m.cols];
+        cvec[m.off_c + j] = (float)(s / (double)m.rows);
+    }
+    __shared__ double sh[256];
+    sh[threadIdx.x] = local;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) mu_out[blockIdx.x] = sh[0] / (double)m.rows;
+}
+
+__global__ __launch_bounds__(256) void k_resid(const float* __restrict__ v_all, const MatRow* __restrict__ mats,
+                                               uint32_t n_mats, uint32_t n_tasks, const float* __restrict__ rvec,
+                                               const float* __restrict__ cvec, const double* __restrict__ mu_all,
+                                               float* __restrict__ residpart)
+{
+    const uint32_t lane = threadIdx.x & 63u, task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (task >= n_tasks) return;
+    const MatTask t = decode_task(mats, n_mats, task);
+    const MatRow& m = mats[t.mat];
+    const double mu = mu_all[t.mat];
+    const float inv_mu = mu != 0.0 ? (float)(1.0 / mu) : 0.f;        // S~ = 0 when mu = 0
+    float cm[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t c = tile_col(t.vec, lane, k);
+        cm[k] = c < t.ncols ? cvec[m.off_c + t.col0 + c] * inv_mu : 0.f;
+    }
+    const float* row = v_all + m.state_start + (uint64_t)t.row0 * m.cols + t.col0;
+    const float* rr = rvec + m.off_r + t.row0;
+    float res = 0.f, s2 = 0.f;
+    uint32_t r = t.row0;
+    for (; r + 4 <= t.row1; r += 4) {
+        float x[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float ri = rr[q];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float d = x[q][k] - ri * cm[k];
+                res = __builtin_fmaf(d, d, res);
+                s2 = __builtin_fmaf(x[q][k], x[q][k], s2);
+            }
+        }
+        row += (uint64_t)4 * m.cols; rr += 4;
+    }
+    for (; r < t.row1; ++r) {
+        float x[4];
+        load_tile_row(row, t.vec, lane, t.ncols, x);
+        const float ri = *rr;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float d = x[k] - ri * cm[k];
+            res = __builtin_fmaf(d, d, res);
+            s2 = __builtin_fmaf(x[k], x[k], s2);
+        }
+        row += m.cols; ++rr;
+    }
+    res = wave_sum(res); s2 = wave_sum(s2);
+    if (lane == 0) { residpart[(uint64_t)task * 2] = res; residpart[(uint64_t)task * 2 + 1] = s2; }
+}
+
+__global__ __launch_bounds__(256) void k_resid_finish(const MatRow* __restrict__ mats, const float* __restrict__ residpart,
+                                                      double* __restrict__ rec_all)
+{
+    const MatRow m = mats[blockIdx.x];
+    const uint32_t n = m.n_tiles * m.n_segs;
+    double a = 0.0, b = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += 256) {
+        a += (double)residpart[(uint64_t)(m.first_task + i) * 2];
+        b += (double)residpart[(uint64_t)(m.first_task + i) * 2 + 1];
+    }
+    __shared__ double sa[256], sb[256];
+    sa[threadIdx.x] = a; sb[threadIdx.x] = b;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) { sa[threadIdx.x] += sa[threadIdx.x + w]; sb[threadIdx.x] += sb[threadIdx.x + w]; }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        double* rec = rec_all + (uint64_t)m.block * kRecDoubles;
+        rec[R_FRES] = sa[0]; rec[R_FS2] = sb[0];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 6: distortion C.  p = 1/(sqrt(v) + eps).  Pass 1: sum of p per chunk (-> p-bar per
+// block).  Pass 2: sum of ((p/p-bar - 1) theta)^2 and of theta^2 per chunk.  theta is laid
+// out like the gradient buffer.  Partial rows reuse the step's partial-sum buffer.
+// ---------------------------------------------------------------------------
+
+template <int TT, int PASS>
+__global__ __launch_bounds__(256) void k_distortion(
+    const float* __restrict__ v_all, const typename GradIO<TT>::elem* __restrict__ theta,
+    const Chunk* __restrict__ chunks, const BlockRow* __restrict__ rows, const double* __restrict__ rec_all,
+    float* __restrict__ partials, float eps)
+{
+    typedef GradIO<TT> IO;
+    const Chunk ck = chunks[blockIdx.x];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const typename IO::elem* tsrc = theta + ck.grad_start;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(tsrc) & IO::kAlignMask) == 0;
+    float inv_pbar = 0.f;
+    if (PASS == 2) inv_pbar = (float)((double)rows[ck.block].numel / rec_all[(uint64_t)ck.block * kRecDoubles + R_PSUM]);
+    float a0 = 0.f, a1 = 0.f;
+    for (uint32_t e = threadIdx.x * 4; e < ck.count; e += 1024) {
+        const f4 vv = ld_stream<f4>(v_all + ck.state_start + e);
+        const float v[4] = {vv.x, vv.y, vv.z, vv.w};
+        float th[4] = {0.f, 0.f, 0.f, 0.f};
+        if (PASS == 2) {
+            if (vec_ok && e + 4 <= ck.count) IO::load4(tsrc + e, th);
+            else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) th[j] = (e + j < ck.count) ? IO::load1(tsrc + e + j) : 0.f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (e + j < ck.count) {                          // padding coordinates are not part of the block
+                const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v[j]) + eps);
+                if (PASS == 1) a0 += p;
+                else {
+                    const float x = (p * inv_pbar - 1.0f) * th[j];
+                    a0 = __builtin_fmaf(x, x, a0);
+                    a1 = __builtin_fmaf(th[j], th[j], a1);
+                }
+            }
+        }
+    }
+    __shared__ float red[4][2];
+    a0 = wave_sum(a0); a1 = wave_sum(a1);
+    if (lane == 0) { red[wave][0] = a0; red[wave][1] = a1; }
+    __syncthreads();
+    if (threadIdx.x < 2)
+        partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] =
+            (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+// Per block: fp64 sum of the first `ncols` entries of its partial rows into rec[dst .. dst+ncols).
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partials, const BlockRow* __restrict__ rows,
+                                                         double* __restrict__ rec_all, uint32_t ncols, uint32_t dst)
+{
+    const BlockRow br = rows[blockIdx.x];
+    __shared__ double sh[256];
+    for (uint32_t col = 0; col < ncols; ++col) {
+        double a = 0.0;
+        for (uint32_t c = threadIdx.x; c < br.n_chunks; c += 256) a += (double)partials[(uint64_t)(br.first_chunk + c) * kNumSums + col];
+        sh[threadIdx.x] = a;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) rec_all[(uint64_t)blockIdx.x * kRecDoubles + dst + col] = sh[0];
+        __syncthreads();
+    }
+}
+
 }  // namespace baoc
 
 // ---------------------------------------------------------------------------
@@ -487,6 +764,9 @@ using namespace baoc;
 struct Plan {
     uint64_t n_chunks = 0;
     std::vector<BlockRow> rows;
+    std::vector<MatRow> mats;     // matrix blocks (rows*cols == numel), for Eq. 7
+    uint64_t n_tasks = 0;
+    uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
     uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
              off_rec = 0, off_hist = 0, off_selp = 0, off_selr = 0, off_ostat = 0, total = 0;
@@ -565,6 +845,24 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         if (P.n_chunks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
     }
     P.padded = state;
+    // tiles of the matrix blocks (Eq. 7)
+    P.mats.clear(); P.n_tasks = 0;
+    uint64_t n_r = 0, n_c = 0, n_rowpart = 0, n_colpart = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const baoc_block& b = blocks[i];
+        if (!b.rows || !b.cols) continue;
+        MatRow m;
+        m.state_start = P.rows[i].state_start;
+        m.rows = b.rows; m.cols = b.cols;
+        m.n_tiles = (b.cols + kTileCols - 1) / kTileCols; m.n_segs = (b.rows + kTileRows - 1) / kTileRows;
+        m.off_r = n_r; m.off_c = n_c; m.off_rowpart = n_rowpart; m.off_colpart = n_colpart;
+        m.first_task = (uint32_t)P.n_tasks; m.block = i;
+        n_r += b.rows; n_c += b.cols;
+        n_rowpart += (uint64_t)b.rows * m.n_tiles; n_colpart += (uint64_t)m.n_segs * b.cols;
+        P.n_tasks += (uint64_t)m.n_tiles * m.n_segs;
+        if (P.n_tasks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
+        P.mats.push_back(m);
+    }
     const uint64_t gsz = prm->grad_dtype == BAOC_GRAD_F32 ? 4 : 2;
     uint64_t o = 0;
     P.off_m = o;        o = align_up(o + P.padded * 4, 256);
@@ -578,6 +876,13 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_selp = o;     o = align_up(o + (uint64_t)n * 4 * 4, 256);
     P.off_selr = o;     o = align_up(o + (uint64_t)n * 4 * 4, 256);
     P.off_ostat = o;    o = align_up(o + (uint64_t)n * 4 * 4, 256);
+    P.off_mats = o;     o = align_up(o + P.mats.size() * sizeof(MatRow), 256);
+    P.off_mu = o;       o = align_up(o + P.mats.size() * 8, 256);
+    P.off_rvec = o;     o = align_up(o + n_r * 4, 256);
+    P.off_cvec = o;     o = align_up(o + n_c * 4, 256);
+    P.off_rowpart = o;  o = align_up(o + n_rowpart * 4, 256);
+    P.off_colpart = o;  o = align_up(o + n_colpart * 4, 256);
+    P.off_residpart = o; o = align_up(o + P.n_tasks * 2 * 4, 256);
     P.total = o;
     return BAOC_OK;
 }
@@ -616,8 +921,10 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     const Plan& P = h->plan;
     // The first step treats m, v and g_prev as zero without reading them and writes all of them
     // (padding included), so only the small tail of the workspace is cleared here.
-    hipError_t e = hipMemset(h->ws + P.off_rec, 0, P.total - P.off_rec);
+    hipError_t e = hipMemset(h->ws + P.off_rec, 0, P.off_mats - P.off_rec);
     if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_rows, P.rows.data(), P.rows.size() * sizeof(BlockRow), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !P.mats.empty())
+        e = hipMemcpy(h->ws + P.off_mats, P.mats.data(), P.mats.size() * sizeof(MatRow), hipMemcpyHostToDevice);
     if (e == hipSuccess) {
         hipLaunchKernelGGL(k_build_chunks, dim3((uint32_t)((P.n_chunks + 255) / 256)), dim3(256), 0, nullptr,
                            reinterpret_cast<const BlockRow*>(h->ws + P.off_rows), n_blocks,
@@ -681,6 +988,11 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
     if (risk_params) rp = *risk_params; else baoc_risk_params_default(&rp);
     if (!(rp.A_high != rp.A_low) || !(rp.rho_high != rp.rho_low) || !(rp.eta_high != rp.eta_low)) return BAOC_ERR_INVALID;
 
+    const bool want_F = !rp.F_raw && rp.compute_F && !h->plan.mats.empty();
+    const bool want_C = !rp.C_raw && rp.d_theta_flat;
+    if (want_C && (rp.theta_numel < h->max_end || (rp.theta_dtype != BAOC_GRAD_F32 && rp.theta_dtype != BAOC_GRAD_BF16)))
+        return BAOC_ERR_INVALID;
+
     const Plan& P = h->plan;
     const uint32_t N = (uint32_t)P.rows.size(), nch = (uint32_t)P.n_chunks;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -705,6 +1017,38 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
     hipLaunchKernelGGL(k_hist<3>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
     hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
 
+    if (want_F) {
+        const MatRow* mats = reinterpret_cast<const MatRow*>(h->ws + P.off_mats);
+        const uint32_t n_mats = (uint32_t)P.mats.size(), n_tasks = (uint32_t)P.n_tasks;
+        float* rvec = reinterpret_cast<float*>(h->ws + P.off_rvec);
+        float* cvec = reinterpret_cast<float*>(h->ws + P.off_cvec);
+        float* rowpart = reinterpret_cast<float*>(h->ws + P.off_rowpart);
+        float* colpart = reinterpret_cast<float*>(h->ws + P.off_colpart);
+        float* residpart = reinterpret_cast<float*>(h->ws + P.off_residpart);
+        double* mu = reinterpret_cast<double*>(h->ws + P.off_mu);
+        hipLaunchKernelGGL(k_rowcol, dim3((n_tasks + 3) / 4), dim3(256), 0, st, v, mats, n_mats, n_tasks, rowpart, colpart);
+        hipLaunchKernelGGL(k_rowcol_finish, dim3(n_mats), dim3(256), 0, st, mats, rowpart, colpart, rvec, cvec, mu);
+        hipLaunchKernelGGL(k_resid, dim3((n_tasks + 3) / 4), dim3(256), 0, st, v, mats, n_mats, n_tasks, rvec, cvec, mu, residpart);
+        hipLaunchKernelGGL(k_resid_finish, dim3(n_mats), dim3(256), 0, st, mats, residpart, reinterpret_cast<double*>(h->ws + P.off_rec));
+    }
+    if (want_C) {
+        float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
+        double* rec = reinterpret_cast<double*>(h->ws + P.off_rec);
+        const float epsf = (float)h->params.eps;
+        if (rp.theta_dtype == BAOC_GRAD_F32) {
+            const float* th = static_cast<const float*>(rp.d_theta_flat);
+            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 1>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
+            hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 1u, (uint32_t)R_PSUM);
+            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 2>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
+        } else {
+            const uint16_t* th = static_cast<const uint16_t*>(rp.d_theta_flat);
+            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 1>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
+            hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 1u, (uint32_t)R_PSUM);
+            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 2>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
+        }
+        hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 2u, (uint32_t)R_CNUM);
+    }
+
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h->h_rec.data(), h->ws + P.off_rec, h->h_rec.size() * 8, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipMemcpyAsync(h->h_ostat.data(), ostat, h->h_ostat.size() * 4, hipMemcpyDeviceToHost, st);
@@ -722,7 +1066,11 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
         for (int t = 0; t < 4; ++t) r.order_stat[t] = h->h_ostat[(size_t)i * 4 + t];
         const double p10 = 0.1 * (double)(r.numel - 1), p90 = 0.9 * (double)(r.numel - 1);
         r.frac10 = p10 - std::floor(p10); r.frac90 = p90 - std::floor(p90);
-        block_metrics(r, h->params.eps, rp, rp.C_raw ? rp.C_raw[i] : 0.0, rp.F_raw ? rp.F_raw[i] : 0.0, &stats[i]);
+        const double eps = h->params.eps;
+        double C_raw = rp.C_raw ? rp.C_raw[i] : 0.0, F_raw = rp.F_raw ? rp.F_raw[i] : 0.0;
+        if (want_C) C_raw = std::sqrt(rec[R_CNUM]) / (std::sqrt(rec[R_CDEN]) + eps);                  // Eq. 6
+        if (want_F && h->blocks[i].rows) F_raw = std::sqrt(rec[R_FRES]) / (std::sqrt(rec[R_FS2]) + eps);   // Eq. 7
+        block_metrics(r, eps, rp, C_raw, F_raw, &stats[i]);
     }
     if (out_stats) std::memcpy(out_stats, stats.data(), sizeof(baoc_block_stats) * N);
     if (out_risk)

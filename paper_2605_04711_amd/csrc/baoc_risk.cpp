@@ -56,6 +56,7 @@ void block_metrics(const RawBlock& r, double eps, const baoc_risk_params& rp,
     o->s_rho = clip((o->rho_bar - rp.rho_low) / (rp.rho_high - rp.rho_low), 0.0, 1.0);            // Eq. 14
     o->s_snr = clip((std::log(1.0 + o->snr) - rp.eta_low) / (rp.eta_high - rp.eta_low), 0.0, 1.0); // Eq. 16
     o->s_M = rp.use_snr_gate ? o->s_rho * o->s_snr : o->s_rho;                                    // Eq. 17
+    o->C = C_raw; o->F = F_raw;
     o->C_tilde = std::log(1.0 + C_raw);                                                           // Eq. 18
     o->s_F = clip(F_raw, 0.0, 1.0);                                                               // Eq. 19
 }
@@ -82,4 +83,5 @@ extern "C" void baoc_risk_params_default(baoc_risk_params* p)
     p->use_snr_gate = 1;
     p->lambda_pref = 0.0;
     p->pref_mask = nullptr; p->C_raw = nullptr; p->F_raw = nullptr;
+    p->compute_F = 1; p->d_theta_flat = nullptr; p->theta_numel = 0; p->theta_dtype = BAOC_GRAD_F32;
 }

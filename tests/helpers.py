@@ -53,9 +53,18 @@ class OracleRunner:
         slices = {i: to_host_bits(buf[self.blocks[i][0]:self.blocks[i][0] + self.blocks[i][1]]) for i in self.only}
         list(self.pool.map(lambda i: self.state[i].step(slices[i]), self.only))
 
-    def finalize(self, configs, rp=None, pref_mask=None):
+    def finalize(self, configs, rp=None, pref_mask=None, shapes=None, theta=None):
+        """shapes: (rows, cols) per block -> F from Eq. 7; theta: flat device tensor -> C from Eq. 6."""
         rp = rp or oracle.default_risk_params()
-        stats = list(self.pool.map(lambda i: self.state[i].finalize(rp), self.only))
+
+        def one(i):
+            F = self.state[i].structure_residual(*shapes[i]) if shapes is not None else 0.0
+            C = 0.0
+            if theta is not None:
+                o, n = self.blocks[i]
+                C = self.state[i].distortion(to_host_bits(theta[o:o + n]))
+            return self.state[i].finalize(rp, C_raw=C, F_raw=F)
+        stats = list(self.pool.map(one, self.only))
         risk = np.array([[oracle.phi(st, c, bool(pref_mask[k]) if pref_mask is not None else False, rp)
                           for k, c in enumerate(configs)] for st in stats])
         return dict(zip(self.only, stats)), risk

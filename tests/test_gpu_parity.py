@@ -21,7 +21,7 @@ def env():
     return dict(torch=torch, B=B, binding=binding, device=device)
 
 
-def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED):
+def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED, theta_dtype=None):
     torch, binding, device = env["torch"], env["binding"], env["device"]
     params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=chunk_groups)
     prof = binding.Profiler(w.blocks, params)
@@ -31,8 +31,12 @@ def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED):
         device.fill(w, buf, seed, t)
         prof.step(buf)
         orc.step_from_device(buf)
-    stats, risk = prof.finalize(w.configs)
-    ostats, orisk = orc.finalize(w.configs)
+    theta = None
+    if theta_dtype is not None:                              # parameters for Eq. 6, same layout as the gradients
+        gen = torch.Generator(device="cuda:0"); gen.manual_seed(1234 + seed)
+        theta = (0.02 * torch.randn(w.buffer_numel, device="cuda:0", generator=gen)).to(theta_dtype)
+    stats, risk = prof.finalize(w.configs, theta=theta)
+    ostats, orisk = orc.finalize(w.configs, shapes=[(b.rows, b.cols) for b in w.blocks], theta=theta)
     for row, i in enumerate(orc.only):
         assert_stats_close(stats[i], ostats[i], f"{w.name} block {i} ({w.blocks[i].name}, d={w.blocks[i].numel})")
         assert_risk_close(risk[i], orisk[row], f"{w.name} block {i}")
@@ -63,12 +67,19 @@ def test_tiny_all_blocks_all_steps_and_allocation(env):
 
 def test_tiny_bf16_gradients(env):
     w = W.make("tiny"); w.grad_dtype = "bf16"
-    run_both(env, w, 6)
+    run_both(env, w, 6, theta_dtype=env["torch"].bfloat16)
 
 
 def ragged_workload(dtype, pad, reverse=False):
     sizes = [1, 3, 63, 64, 255, 256, 257, 1000, 4099, 9408, 70001, 5, 1024 * 33 + 7]
-    blocks = [W.BlockSpec(f"r{i}", n) for i, n in enumerate(sizes)]
+    shapes = {3: (8, 8), 4: (5, 51), 5: (256, 1), 7: (10, 100), 8: (4099, 1), 9: (64, 147), 10: (70001, 1), 12: (73, 463)}
+    blocks = []
+    for i, n in enumerate(sizes):
+        r, c = shapes.get(i, (0, 0))
+        if r * c != n:
+            r, c = (0, 0)
+        blocks.append(W.BlockSpec(f"r{i}", n, r, c))
+    blocks.append(W._mat("wide", 3, 1027)); blocks.append(W._mat("tall", 1030, 3)); blocks.append(W._mat("sq", 300, 260))
     w = W.Workload("ragged", blocks, 5, dtype, "cycle", **W.K6)
     W.layout(w, pad); W.draw_stream_params(w, 5)
     if reverse:
@@ -79,12 +90,14 @@ def ragged_workload(dtype, pad, reverse=False):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("pad,chunk_groups,reverse", [(1, 2, False), (64, 0, True), (3, 1, False)])
 def test_ragged_blocks_unaligned_offsets_gaps_and_order(env, dtype, pad, chunk_groups, reverse):
-    run_both(env, ragged_workload(dtype, pad, reverse), 5, chunk_groups=chunk_groups)
+    torch = env["torch"]
+    run_both(env, ragged_workload(dtype, pad, reverse), 5, chunk_groups=chunk_groups,
+             theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
 
 
 def test_resnet50_all_blocks_all_steps(env):
     w = W.make("resnet50")
-    run_both(env, w, w.T)
+    run_both(env, w, w.T, theta_dtype=env["torch"].float32)
 
 
 def test_gpt2_small_all_steps(env):
