@@ -78,6 +78,10 @@ def lib():
         L.orc_block_structure_residual.argtypes = [vp, u32, u32]
         L.orc_block_distortion.restype = f64
         L.orc_block_distortion.argtypes = [vp, vp]
+        L.orc_sample_count.restype = u64
+        L.orc_sample_count.argtypes = [u64, f64]
+        L.orc_sample_indices.restype = None
+        L.orc_sample_indices.argtypes = [u64, u64, u64, u32, vp]
         L.orc_bf16_round.restype = f32
         L.orc_bf16_round.argtypes = [f32]
         L.orc_q8_code.restype = f32
@@ -192,6 +196,19 @@ class Profiler:
             rows.append([phi(st, c, bool(pref_mask[k]) if pref_mask is not None else False, rp)
                          for k, c in enumerate(configs)])
         return stats, np.array(rows, dtype=np.float64).reshape(len(idx), len(configs))
+
+
+def sample_count(d, s):
+    """|Omega| = ceil(s d), clamped to [1, d] (Sec. 3.1)."""
+    return lib().orc_sample_count(int(d), float(s))
+
+
+def sample_indices(d, s, seed, block):
+    """The fixed index set Omega of one block (ascending uint64 array)."""
+    k = sample_count(d, s)
+    out = np.zeros(k, np.uint64)
+    lib().orc_sample_indices(int(d), k, int(seed), int(block), out.ctypes.data)
+    return out
 
 
 def phi(stats, cfg, preferred=False, rp=None):

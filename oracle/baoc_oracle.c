@@ -209,6 +209,41 @@ int orc_block_step_bf16(orc_block *b, const uint16_t *g)
 }
 
 /* ------------------------------------------------------------------ */
+/* Sparse coordinate sampling (Sec. 3.1)                               */
+/* ------------------------------------------------------------------ */
+
+/* |Omega_i| = ceil(s d_i), at least 1 and at most d_i. */
+uint64_t orc_sample_count(uint64_t d, double s)
+{
+    double k = ceil(s * (double)d);
+    if (!(k >= 1.0)) k = 1.0;
+    if (k > (double)d) k = (double)d;
+    return (uint64_t)k;
+}
+
+static uint64_t mix64(uint64_t x)
+{
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+/* Omega_i is drawn once and then fixed.  Reading of "sample a subset of coordinates":
+   a stratified uniform draw -- cut {0..d-1} into k = |Omega_i| strata
+   [floor(j d / k), floor((j+1) d / k)) and take one coordinate of each, chosen by a
+   64-bit mix of (seed, block, j).  Indices come out ascending; s = 1 gives every coordinate. */
+void orc_sample_indices(uint64_t d, uint64_t k, uint64_t seed, uint32_t block, uint64_t *out)
+{
+    const uint64_t key = mix64(mix64(seed) + block);
+    for (uint64_t j = 0; j < k; ++j) {
+        uint64_t lo = (uint64_t)(((unsigned __int128)j * d) / k);
+        uint64_t hi = (uint64_t)(((unsigned __int128)(j + 1) * d) / k);
+        uint64_t h = mix64(key + (j + 1) * 0x9E3779B97F4A7C15ull);
+        out[j] = lo + h % (hi - lo);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Finalize: raw metrics, normalisation (App. A) and risk (Eq. 9)      */
 /* ------------------------------------------------------------------ */
 
