@@ -170,6 +170,42 @@ int baoc_profile_state(const baoc_profiler* p, uint32_t block,
 /* Release the handle (host memory only; the workspace stays the caller's). */
 int baoc_profile_end(baoc_profiler* p);
 
+/* ---- Sparse coordinate sampling (Sec. 3.1) --------------------------------
+ * The paper profiles a fixed subset Omega_i of each block, |Omega_i| =
+ * ceil(ratio * d_i) (at least 1), drawn once.  Here: a stratified uniform draw
+ * (one coordinate out of each of |Omega_i| equal strata, by a 64-bit mix of
+ * (seed, block, stratum)), indices ascending.  The sampler packs g[Omega] of all
+ * blocks into a compact buffer; the profiler then runs on that buffer with the
+ * compact block layout.  Compact blocks carry no matrix shape. */
+typedef struct baoc_sampler baoc_sampler;
+
+/* Compact layout for this ratio (0 < ratio <= 1): out_compact (HOST, n_blocks, may
+ * be NULL) receives offset/numel of each block in the compact buffer (starts on
+ * multiples of 64 elements), out_compact_numel its length, out_workspace_bytes the
+ * device bytes the sampler needs (tables + 8 bytes per sampled coordinate). */
+int baoc_sample_layout(const baoc_block* blocks, uint32_t n_blocks, double ratio,
+                       baoc_block* out_compact, uint64_t* out_compact_numel,
+                       uint64_t* out_workspace_bytes);
+
+/* Draw Omega on the device into d_workspace (DEVICE, 256-byte aligned, caller
+ * owned, kept until baoc_sample_end).  Synchronous on the null stream.
+ * Errors: INVALID, WORKSPACE, UNSUPPORTED, HIP. */
+int baoc_sample_begin(const baoc_block* blocks, uint32_t n_blocks, double ratio, uint64_t seed,
+                      void* d_workspace, uint64_t workspace_bytes, baoc_sampler** out);
+
+/* d_compact[compact offset of block i + j] = d_grad_flat[Omega_i[j]] for every block,
+ * enqueued on hip_stream.  Both buffers DEVICE, of dtype grad_dtype; gaps of the
+ * compact buffer are left untouched.  Errors: INVALID (buffers too short), HIP. */
+int baoc_sample_gather(baoc_sampler* s, const void* d_grad_flat, uint64_t grad_numel,
+                       uint32_t grad_dtype, void* d_compact, uint64_t compact_numel,
+                       void* hip_stream);
+
+/* Device view of Omega_i as absolute element positions in the flat buffer. */
+int baoc_sample_indices(const baoc_sampler* s, uint32_t block,
+                        const uint64_t** d_indices, uint64_t* count);
+
+int baoc_sample_end(baoc_sampler* s);
+
 /* Exact solution of the allocation problem of Eq. 2 (a multiple-choice knapsack
  * with a memory row and a time row) on the integer image of the instance:
  *   phi = llround(1e9 * clamp(risk, -1e6, 1e6)),  tau = llround(1e6 * time_cost),

@@ -82,6 +82,11 @@ def load_library():
                                         C.POINTER(BlockStats), vp, vp]
     L.baoc_profile_state.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     L.baoc_profile_end.argtypes = [vp]
+    L.baoc_sample_layout.argtypes = [C.POINTER(Block), u32, f64, C.POINTER(Block), C.POINTER(u64), C.POINTER(u64)]
+    L.baoc_sample_begin.argtypes = [C.POINTER(Block), u32, f64, u64, vp, u64, C.POINTER(vp)]
+    L.baoc_sample_gather.argtypes = [vp, vp, u64, u32, vp, u64, vp]
+    L.baoc_sample_indices.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(u64)]
+    L.baoc_sample_end.argtypes = [vp]
     L.baoc_allocate.argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp, C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
     L.baoc_allocate_set_node_limit.argtypes = [u64]
     L.baoc_allocate_set_node_limit.restype = None
@@ -232,6 +237,65 @@ class Profiler:
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:
             self.lib.baoc_profile_end(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Sampler:
+    """baoc_sample_* : fixed index sets Omega_i (Sec. 3.1) and the gather into a compact buffer.
+
+    compact_blocks is the layout to hand to Profiler for the compact buffer."""
+
+    def __init__(self, blocks, ratio, seed=0, device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        self.n_blocks = len(blocks)
+        self._blocks = _block_array(blocks)
+        compact = (Block * self.n_blocks)()
+        cn, wb = C.c_uint64(), C.c_uint64()
+        _check(self.lib.baoc_sample_layout(self._blocks, self.n_blocks, float(ratio), compact, C.byref(cn), C.byref(wb)),
+               "baoc_sample_layout")
+        self.compact_blocks = [(b.offset, b.numel, 0, 0) for b in compact]
+        self.compact_numel = cn.value
+        self.device = torch.device(device)
+        self.workspace = torch.empty(max(wb.value, 256), dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.baoc_sample_begin(self._blocks, self.n_blocks, float(ratio), int(seed),
+                                              self.workspace.data_ptr(), self.workspace.numel(), C.byref(self._h)),
+                   "baoc_sample_begin")
+
+    def gather(self, grad, out=None, stream=None):
+        torch = self._torch
+        if grad.dtype not in (torch.float32, torch.bfloat16) or not grad.is_contiguous() or grad.device != self.device:
+            raise TypeError(f"gradient must be a contiguous float32 or bfloat16 tensor on {self.device}")
+        if out is None:
+            out = torch.zeros(self.compact_numel, dtype=grad.dtype, device=self.device)
+        if out.dtype != grad.dtype or not out.is_contiguous() or out.device != self.device:
+            raise TypeError("compact buffer must match the gradient's dtype and device")
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        _check(self.lib.baoc_sample_gather(self._h, grad.data_ptr(), grad.numel(),
+                                           GRAD_F32 if grad.dtype == torch.float32 else GRAD_BF16,
+                                           out.data_ptr(), out.numel(), s.cuda_stream), "baoc_sample_gather")
+        return out
+
+    def indices(self, block):
+        """Omega of one block as an int64 torch view (absolute positions in the flat buffer)."""
+        torch = self._torch
+        p, n = C.c_void_p(), C.c_uint64()
+        _check(self.lib.baoc_sample_indices(self._h, block, C.byref(p), C.byref(n)), "baoc_sample_indices")
+        off = p.value - self.workspace.data_ptr()
+        return self.workspace[off:off + 8 * n.value].view(torch.int64)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self.lib.baoc_sample_end(self._h)
             self._h = C.c_void_p()
 
     def __del__(self):

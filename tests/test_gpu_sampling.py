@@ -1,0 +1,75 @@
+"""Sparse coordinate sampling front end against the oracle (index sets and gathered values bit exact,
+statistics of the sampled stream within the statistics tolerance)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import assert_stats_close, oracle_params, to_host_bits
+from synth import workloads as W
+from test_gpu_parity import env, ragged_workload  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("ratio", [0.001, 0.05, 1.0])
+def test_index_sets_gather_and_sampled_statistics(env, dtype, ratio):  # noqa: F811
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload(dtype, 1)
+    seed = 17
+    smp = binding.Sampler(w.blocks, ratio, seed)
+    idx = []
+    for i, b in enumerate(w.blocks):
+        want = oracle.sample_indices(b.numel, ratio, seed, i) + np.uint64(b.offset)
+        got = smp.indices(i).cpu().numpy().view(np.uint64)
+        assert np.array_equal(got, want), f"Omega of block {i}"
+        assert smp.compact_blocks[i][1] == oracle.sample_count(b.numel, ratio)
+        idx.append(want.astype(np.int64))
+    params = binding.default_profile_params(grad_dtype=1 if dtype == "bf16" else 0)
+    prof = binding.Profiler(smp.compact_blocks, params)
+    orc = [oracle.Block(len(ix), **oracle_params(params)) for ix in idx]
+    buf = device.new_buffer(w)
+    compact = None
+    for t in range(1, 5):
+        device.fill(w, buf, 3, t)
+        compact = smp.gather(buf, compact)
+        host, chost = to_host_bits(buf), to_host_bits(compact)
+        for i, ix in enumerate(idx):
+            o, n = smp.compact_blocks[i][0], smp.compact_blocks[i][1]
+            assert np.array_equal(chost[o:o + n], host[ix]), f"gathered values of block {i}"
+            orc[i].step(host[ix])
+        prof.step(compact)
+    stats, _ = prof.finalize()
+    for i in range(len(idx)):
+        assert_stats_close(stats[i], orc[i].finalize(), f"sampled block {i} ratio {ratio}")
+
+
+def test_sampler_rejects_bad_arguments(env):  # noqa: F811
+    torch, binding = env["torch"], env["binding"]
+    for ratio in (0.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(binding.BaocError) as e:
+            binding.Sampler([(0, 100)], ratio)
+        assert e.value.status == binding.ERR_INVALID
+    smp = binding.Sampler([(0, 1000), (1000, 50)], 0.1)
+    with pytest.raises(binding.BaocError) as e:
+        smp.gather(torch.zeros(1049, device="cuda:0"))
+    assert e.value.status == binding.ERR_INVALID
+    with pytest.raises(binding.BaocError) as e:
+        smp.gather(torch.zeros(1050, device="cuda:0"), torch.zeros(64, device="cuda:0"))
+    assert e.value.status == binding.ERR_INVALID
+
+
+def test_full_size_sampling_of_the_7b_layout(env):  # noqa: F811
+    """s = 0.1 % of the 7B-shaped layout: index sets of sampled blocks bit exact, gather bit exact."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = W.make("llama7b")
+    smp = binding.Sampler(w.blocks, 0.001, 5)
+    buf = device.fill(w, device.new_buffer(w), 1, 1)
+    compact = smp.gather(buf)
+    torch.cuda.synchronize()
+    for i in (0, 1, 2, 150, 289, 290):
+        b = w.blocks[i]
+        want = oracle.sample_indices(b.numel, 0.001, 5, i).astype(np.int64) + b.offset
+        assert np.array_equal(smp.indices(i).cpu().numpy(), want)
+        o, n = smp.compact_blocks[i][0], smp.compact_blocks[i][1]
+        assert torch.equal(compact[o:o + n], buf[torch.from_numpy(want).cuda()])
