@@ -226,6 +226,22 @@ int baoc_allocate(const double* risk, const int64_t* mem_cost_bytes, const doubl
                   const uint8_t* forbidden,
                   uint32_t* out_choice, double* out_objective, int64_t* out_mem, double* out_time);
 
+/* Block partitioning (App. C.2, Algorithm 2), host code.  Units are the structural
+ * candidates in forward order: unit j has unit_numel[j] > 0 parameters and a normalised
+ * diagnostic vector z[j*n_stats .. ] (e.g. the App. A signals that a profile of the units
+ * returned).  Delta(U_a,U_b) = max_k w_k |z_a,k - z_b,k| (weights NULL = all 1); tau = upper
+ * quartile of Delta over all unit pairs; n_min = alpha * total parameters (0 <= alpha <= 1).
+ * Undersized candidates are merged into their statistically closest neighbour, adjacent
+ * candidates stay separate only when Delta > tau and both reach n_min, formed blocks are
+ * split where their two sides differ by more than tau, and what is still undersized is
+ * merged again.  out_block_of_unit (n_units) receives ascending block ids from 0; a
+ * block's statistics are the parameter-weighted mean of its units.  All pointers HOST;
+ * out_n_blocks and out_tau may be NULL.  Errors: INVALID (null, zero sizes, non-finite z,
+ * negative weights, alpha outside [0,1]). */
+int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
+                   const double* weights, double alpha,
+                   uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau);
+
 /* Search-node cap of baoc_allocate for this thread's later calls (0 = default). */
 void baoc_allocate_set_node_limit(uint64_t max_nodes);
 

@@ -88,6 +88,7 @@ def load_library():
     L.baoc_sample_indices.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(u64)]
     L.baoc_sample_end.argtypes = [vp]
     L.baoc_allocate.argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp, C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
+    L.baoc_partition.argtypes = [vp, vp, u32, u32, vp, f64, vp, C.POINTER(u32), C.POINTER(f64)]
     L.baoc_allocate_set_node_limit.argtypes = [u64]
     L.baoc_allocate_set_node_limit.restype = None
     L.baoc_status_string.argtypes = [C.c_int]
@@ -303,6 +304,20 @@ class Sampler:
             self.close()
         except Exception:
             pass
+
+
+def partition(unit_numel, z, weights=None, alpha=0.01):
+    """baoc_partition -> (block id per unit uint32[m], number of blocks, tau)."""
+    numel = np.ascontiguousarray(unit_numel, dtype=np.uint64)
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    m, K = z.shape
+    w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float64)
+    ids = np.zeros(m, np.uint32)
+    nb, tau = C.c_uint32(), C.c_double()
+    rc = load_library().baoc_partition(numel.ctypes.data, z.ctypes.data, m, K, None if w is None else w.ctypes.data,
+                                       float(alpha), ids.ctypes.data, C.byref(nb), C.byref(tau))
+    _check(rc, "baoc_partition")
+    return ids, nb.value, tau.value
 
 
 def allocate(risk, mem_cost_bytes, time_cost, mem_budget_bytes, time_budget_sum, forbidden=None):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbaoc.so")
-SOURCES = ["baoc_profile.hip", "baoc_sample.hip", "baoc_risk.cpp", "baoc_allocate.cpp"]
+SOURCES = ["baoc_profile.hip", "baoc_sample.hip", "baoc_risk.cpp", "baoc_allocate.cpp", "baoc_partition.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

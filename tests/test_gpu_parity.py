@@ -111,6 +111,25 @@ def test_gpt2_small_embeddings_heavy_tailed(env):
     run_both(env, w, 4, only=[0, 1])
 
 
+def test_full_candidate_space_with_soft_preference(env):
+    """21 candidates (Sec. 4.1) and the soft preference of Sec. 3.2 in the risk table."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = W.make("tiny")
+    k21 = W.k21()
+    pref = [1 if n.startswith("adamw") else 0 for n in k21["config_names"]]
+    prof = binding.Profiler(w.blocks)
+    orc = OracleRunner(w.blocks, **oracle_params(prof.params))
+    buf = device.new_buffer(w)
+    for t in range(1, 6):
+        device.fill(w, buf, 2, t); prof.step(buf); orc.step_from_device(buf)
+    rp = binding.default_risk_params(lambda_pref=0.3, gamma=0.2)
+    stats, risk = prof.finalize(k21["configs"], risk_params=rp, pref_mask=pref)
+    orp = oracle.default_risk_params(lambda_pref=0.3, gamma=0.2)
+    ostats, orisk = orc.finalize(k21["configs"], rp=orp, pref_mask=pref, shapes=[(b.rows, b.cols) for b in w.blocks])
+    assert risk.shape == (8, 21)
+    assert_risk_close(risk, orisk, "k21")
+
+
 def test_two_runs_give_identical_bits(env):
     w = ragged_workload("f32", 1)
     a = run_both(env, w, 4, chunk_groups=2)[1]

@@ -160,6 +160,26 @@ def test_allocate_errors_and_exclusions():
     assert list(x) == [1, 0]
 
 
+def test_allocate_full_candidate_space_with_exclusions():
+    """The 7 mechanisms x {32,16,8} bits of Sec. 4.1 (21 candidates), hard exclusion of the SGD family."""
+    k21 = W.k21()
+    K = len(k21["configs"])
+    assert K == 21
+    for _ in range(6):
+        N = int(RNG.integers(8, 30))
+        risk = np.round(RNG.random((N, K)) * 2, 3)
+        mem = RNG.integers(0, 16, (N, K)).astype(np.int64)
+        tc = np.tile(np.round(np.array(k21["time_cost"]) * 4) / 4, (N, 1))
+        fb = np.zeros((N, K), np.uint8)
+        for k, name in enumerate(k21["config_names"]):
+            if name.startswith("sgd"):
+                fb[:, k] = 1                                     # the "no-SGD" diagnostic of App. C
+        bm = int(mem.min(1).sum() + 0.4 * (mem.max(1).sum() - mem.min(1).sum()))
+        got = both(oracle.allocate_dp, risk, mem, tc, bm, 1.3 * N, fb)
+        if got[0] == 0:
+            assert not any(fb[i, got[1][i]] for i in range(N))
+
+
 def test_allocate_node_limit_fails_loudly():
     risk, mem, tc, bm, bt = instance(40, 6, "real")
     B.load_library().baoc_allocate_set_node_limit(3)
