@@ -40,13 +40,16 @@ struct alignas(8) BlockRow {
     uint64_t state_start;
     uint64_t numel;
     uint32_t first_chunk, n_chunks;
-    uint32_t groups_per_chunk, pad_;
+    uint32_t groups_per_chunk;
+    uint32_t vec_first;     // first entry of the block in the list of chunks finalize walks chunk-wise; kNoVec when tiled
     uint64_t rank[4];       // order statistics wanted from v: lo(0.1), lo+1, lo(0.9), lo+1
 };
 
 struct StepConsts {
     float beta_m, beta_v, om_m, om_v, eps_u;
 };
+
+constexpr uint32_t kNoVec = 0xffffffffu;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
@@ -337,7 +340,8 @@ __global__ __launch_bounds__(256) void k_block_reduce(
 // Chunk table from the block rows (one thread per chunk; the owning block by bisection on
 // first_chunk).  A block's groups are split evenly over its chunks, whole groups each.
 __global__ __launch_bounds__(256) void k_build_chunks(const BlockRow* __restrict__ rows, uint32_t n_blocks,
-                                                      Chunk* __restrict__ chunks, uint32_t n_chunks)
+                                                      Chunk* __restrict__ chunks, uint32_t n_chunks,
+                                                      uint32_t* __restrict__ vec_list)
 {
     const uint32_t c = blockIdx.x * 256 + threadIdx.x;
     if (c >= n_chunks) return;
@@ -356,6 +360,7 @@ __global__ __launch_bounds__(256) void k_build_chunks(const BlockRow* __restrict
     ck.count = (uint32_t)(min(r.numel, g1 * kQB) - g0 * kQB);
     ck.block = lo;
     chunks[c] = ck;
+    if (r.vec_first != kNoVec) vec_list[r.vec_first + (c - r.first_chunk)] = c;
 }
 
 __global__ void k_fill_u32(uint32_t* p, uint64_t n, uint32_t val)
@@ -364,6 +369,48 @@ __global__ void k_fill_u32(uint32_t* p, uint64_t n, uint32_t val)
 }
 
 constexpr uint32_t kBins = 2048;
+
+// The four ranks of a block usually share their key prefix pairwise (lo and lo+1 of a quantile fall
+// into one bin).  Elements are matched against the distinct prefixes only; slot_of[t] names the LDS
+// histogram that serves rank t, and the flush adds it to every rank that shares it.
+struct Prefixes { uint32_t pre[4]; uint32_t slot_of[4]; uint32_t n; };
+constexpr uint32_t kNoPrefix = 0xffffffffu;             // never equals a key prefix (at most 22 bits)
+__device__ __forceinline__ Prefixes distinct_prefixes(const uint32_t* __restrict__ sel_prefix, uint32_t block)
+{
+    // fully unrolled with static indices so that everything stays in (scalar) registers
+    Prefixes d;
+    d.n = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) d.pre[j] = kNoPrefix;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const uint32_t p = sel_prefix[block * 4 + t];
+        uint32_t slot = 4;
+#pragma unroll
+        for (int j = 3; j >= 0; --j)
+            if (d.pre[j] == p) slot = j;
+        const bool fresh = slot == 4;
+        if (fresh) slot = d.n;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (fresh && (uint32_t)j == d.n) d.pre[j] = p;
+        if (fresh) d.n += 1;
+        d.slot_of[t] = slot;
+    }
+    return d;
+}
+
+// h[u * nb + bin] += 1 for the distinct prefixes that equal hi; slots 2 and 3 are rarely in use
+__device__ __forceinline__ void count_match(uint32_t* h, const Prefixes& d, uint32_t nb, uint32_t hi, uint32_t bin)
+{
+    if (hi == d.pre[0]) atomicAdd(&h[bin], 1u);
+    if (hi == d.pre[1]) atomicAdd(&h[nb + bin], 1u);
+    if (d.n > 2) {
+        if (hi == d.pre[2]) atomicAdd(&h[2 * nb + bin], 1u);
+        if (hi == d.pre[3]) atomicAdd(&h[3 * nb + bin], 1u);
+    }
+}
+
 constexpr uint32_t kHistGrid = 2048;     // persistent workgroups of the histogram passes (8 per CU)
 
 // Each workgroup walks a contiguous run of chunks and keeps the histogram of the parameter block it
@@ -371,9 +418,10 @@ constexpr uint32_t kHistGrid = 2048;     // persistent workgroups of the histogr
 // the run crosses into another block and at its end.
 template <int PASS>
 __global__ __launch_bounds__(256) void k_hist(
-    const float* __restrict__ v_all, const Chunk* __restrict__ chunks, uint32_t n_chunks,
-    const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all)
+    const float* __restrict__ v_all, const Chunk* __restrict__ chunks, const uint32_t* __restrict__ list,
+    uint32_t n_chunks, const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all)
 {
+    // list == nullptr: every chunk; otherwise the chunks named by list[0 .. n_chunks)
     typedef uint32_t u4 __attribute__((ext_vector_type(4)));
     constexpr int NT = PASS == 1 ? 1 : 4;
     constexpr uint32_t NB = PASS == 3 ? 512 : kBins;
@@ -382,27 +430,37 @@ __global__ __launch_bounds__(256) void k_hist(
     const uint32_t c0 = blockIdx.x * per, c1 = min(n_chunks, c0 + per);
     if (c0 >= c1) return;
     for (uint32_t i = threadIdx.x; i < NT * NB; i += 256) h[i] = 0;
-    uint32_t cur = chunks[c0].block;
-    uint32_t pre[4] = {0, 0, 0, 0};
+    uint32_t cur = chunks[list ? list[c0] : c0].block;
+    Prefixes d;
+    d.n = 0;
     auto load_prefixes = [&]() {
-        if (PASS > 1) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) pre[t] = sel_prefix[cur * 4 + t];
-        }
+        if (PASS > 1) d = distinct_prefixes(sel_prefix, cur);
     };
     auto flush = [&]() {
         __syncthreads();
         uint32_t* out = hist_all + (uint64_t)cur * 4 * kBins;
-        for (uint32_t i = threadIdx.x; i < NT * NB; i += 256) {
-            const uint32_t c = h[i];
-            if (c) { atomicAdd(&out[(i / NB) * kBins + (i % NB)], c); h[i] = 0; }
+        if (PASS == 1) {
+            for (uint32_t i = threadIdx.x; i < NB; i += 256) {
+                const uint32_t c = h[i];
+                if (c) { atomicAdd(&out[i], c); h[i] = 0; }
+            }
+        } else {
+            for (uint32_t i = threadIdx.x; i < NB; i += 256) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {                 // static t: slot_of stays in registers
+                    const uint32_t c = h[d.slot_of[t] * NB + i];
+                    if (c) atomicAdd(&out[t * kBins + i], c);
+                }
+            }
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < NT * NB; i += 256) h[i] = 0;
         }
         __syncthreads();
     };
     load_prefixes();
     __syncthreads();
     for (uint32_t c = c0; c < c1; ++c) {
-        const Chunk ck = chunks[c];
+        const Chunk ck = chunks[list ? list[c] : c];
         if (ck.block != cur) { flush(); cur = ck.block; load_prefixes(); }
         const uint32_t* bits = reinterpret_cast<const uint32_t*>(v_all + ck.state_start);
         for (uint32_t e0 = threadIdx.x * 4; e0 < ck.count; e0 += 4096) {
@@ -423,9 +481,7 @@ __global__ __launch_bounds__(256) void k_hist(
                     } else {
                         const uint32_t hi = PASS == 2 ? key[j] >> 20 : key[j] >> 9;
                         const uint32_t bin = PASS == 2 ? (key[j] >> 9) & 0x7ffu : key[j] & 0x1ffu;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            if (hi == pre[t]) atomicAdd(&h[t * NB + bin], 1u);
+                        count_match(h, d, NB, hi, bin);
                     }
                 }
             }
@@ -477,38 +533,45 @@ __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_a
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 7: structure residual F of a matrix block.  S = v viewed as rows x cols.
-// A task is a tile of up to 256 rows x 256 columns owned by one wavefront: each
-// lane keeps 4 column sums, each row's sum is a DPP reduction.  Pass A gives row
-// and column partial sums, a per-block finish turns them into the means r, c
-// and mu (fp64), pass B accumulates |S - r c^T / mu|^2 and |S|^2 per task.
+// Finalize over matrix blocks, tiled.  A task is a tile of up to 256 rows x 256 columns
+// of v (viewed as rows x cols) owned by one wavefront; a workgroup takes four consecutive
+// tasks of one block.  Two passes over v serve three consumers at once:
+//   pass 1: row / column partial sums (Eq. 7), sum of p = 1/(sqrt(v)+eps) (Eq. 6), first
+//           radix digit histogram (Eq. 4)
+//   pass 2: |S - r c^T / mu|^2 and |S|^2 (Eq. 7), ((p/p-bar - 1) theta)^2 and theta^2 (Eq. 6),
+//           second digit histogram
+// Blocks without a matrix shape are walked chunk-wise by k_hist / k_distortion instead.
 // ---------------------------------------------------------------------------
 
 constexpr uint32_t kTileRows = 256, kTileCols = 256;
 
 struct alignas(8) MatRow {
     uint64_t state_start;                 // first coordinate of the block in v
+    uint64_t grad_start;                  // the block's offset in the caller's flat buffers (theta)
     uint64_t off_r, off_c;                // into the r / c vectors (floats)
     uint64_t off_rowpart, off_colpart;    // into the partial-sum arrays (floats)
     uint32_t rows, cols, n_tiles, n_segs;
-    uint32_t first_task, block;
+    uint32_t first_task, first_quad, block, pad_;
 };
 
-struct MatTask { uint32_t mat, row0, row1, col0, ncols, tile, seg; bool vec; };
+struct MatTask { uint32_t mat, task, row0, row1, col0, ncols, tile, seg; bool vec, valid; };
 
-__device__ __forceinline__ MatTask decode_task(const MatRow* __restrict__ mats, uint32_t n_mats, uint32_t task)
+// Workgroup `quad` -> its block and this wavefront's task (tile index fastest).
+__device__ __forceinline__ MatTask decode_quad(const MatRow* __restrict__ mats, uint32_t n_mats, uint32_t quad, uint32_t wave)
 {
     uint32_t lo = 0, hi = n_mats - 1;
     while (lo < hi) {
         const uint32_t mid = (lo + hi + 1) >> 1;
-        if (mats[mid].first_task <= task) lo = mid; else hi = mid - 1;
+        if (mats[mid].first_quad <= quad) lo = mid; else hi = mid - 1;
     }
     const MatRow& m = mats[lo];
-    const uint32_t local = task - m.first_task;
+    const uint32_t local = (quad - m.first_quad) * 4 + wave;
     MatTask t;
-    t.mat = lo; t.seg = local / m.n_tiles; t.tile = local % m.n_tiles;
-    t.row0 = t.seg * kTileRows; t.row1 = min(m.rows, t.row0 + kTileRows);
-    t.col0 = t.tile * kTileCols; t.ncols = min(kTileCols, m.cols - t.col0);
+    t.mat = lo; t.valid = local < m.n_tiles * m.n_segs;
+    t.task = m.first_task + local;
+    t.seg = local / m.n_tiles; t.tile = local % m.n_tiles;
+    t.row0 = t.seg * kTileRows; t.row1 = t.valid ? min(m.rows, t.row0 + kTileRows) : t.row0;
+    t.col0 = t.tile * kTileCols; t.ncols = t.valid ? min(kTileCols, m.cols - t.col0) : 0;
     t.vec = (m.cols & 3u) == 0;           // rows start 16-byte aligned (blocks start on 1 KB)
     return t;
 }
@@ -531,55 +594,97 @@ __device__ __forceinline__ void load_tile_row(const float* __restrict__ row, boo
     }
 }
 
-__global__ __launch_bounds__(256) void k_rowcol(const float* __restrict__ v_all, const MatRow* __restrict__ mats,
-                                                uint32_t n_mats, uint32_t n_tasks,
-                                                float* __restrict__ rowpart, float* __restrict__ colpart)
+template <int TT>
+__device__ __forceinline__ void load_tile_theta(const typename GradIO<TT>::elem* __restrict__ row, bool vec, bool aligned,
+                                                uint32_t lane, uint32_t ncols, float x[4])
 {
-    const uint32_t lane = threadIdx.x & 63u, task = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (task >= n_tasks) return;
-    const MatTask t = decode_task(mats, n_mats, task);
-    const MatRow& m = mats[t.mat];
-    const float* row = v_all + m.state_start + (uint64_t)t.row0 * m.cols + t.col0;
-    float cs[4] = {0.f, 0.f, 0.f, 0.f};
-    float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
-    uint32_t r = t.row0;
-    for (; r + 4 <= t.row1; r += 4) {                       // four rows in flight
-        float x[4][4];
+    // column ownership follows v's (vec: 4 consecutive columns per lane); `aligned` only picks the load width
+    typedef GradIO<TT> IO;
+    if (vec) {
+        if (4 * lane < ncols) {
+            if (aligned) IO::load4(row + 4 * lane, x);
+            else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) cs[k] += x[q][k];
-            const float rs = wave_sum((x[q][0] + x[q][1]) + (x[q][2] + x[q][3]));
-            if (lane == 0) rp[(uint64_t)q * m.n_tiles] = rs;
+                for (int k = 0; k < 4; ++k) x[k] = IO::load1(row + 4 * lane + k);
+            }
+        } else {
+            x[0] = x[1] = x[2] = x[3] = 0.f;
         }
-        row += (uint64_t)4 * m.cols; rp += (uint64_t)4 * m.n_tiles;
-    }
-    for (; r < t.row1; ++r) {
-        float x[4];
-        load_tile_row(row, t.vec, lane, t.ncols, x);
+    } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) cs[k] += x[k];
-        const float rs = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
-        if (lane == 0) *rp = rs;
-        row += m.cols; rp += m.n_tiles;
-    }
-    float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t c = tile_col(t.vec, lane, k);
-        if (c < t.ncols) cp[c] = cs[k];
+        for (int k = 0; k < 4; ++k) x[k] = (lane + 64 * k < ncols) ? IO::load1(row + lane + 64 * k) : 0.f;
     }
 }
 
-// r_i, c_j (fp32 for pass B) and mu (fp64) of one matrix block from the partial sums.
-__global__ __launch_bounds__(256) void k_rowcol_finish(const MatRow* __restrict__ mats, const float* __restrict__ rowpart,
-                                                       const float* __restrict__ colpart, float* __restrict__ rvec,
-                                                       float* __restrict__ cvec, double* __restrict__ mu_out)
+__global__ __launch_bounds__(256) void k_tile_pass1(
+    const float* __restrict__ v_all, const MatRow* __restrict__ mats, uint32_t n_mats,
+    float* __restrict__ rowpart, float* __restrict__ colpart, float* __restrict__ psumpart,
+    uint32_t* __restrict__ hist_all, float eps, bool want_p)
+{
+    __shared__ uint32_t h[kBins];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    for (uint32_t i = threadIdx.x; i < kBins; i += 256) h[i] = 0;
+    const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
+    const MatRow& m = mats[t.mat];
+    __syncthreads();
+    if (t.valid) {
+        const float* row = v_all + m.state_start + (uint64_t)t.row0 * m.cols + t.col0;
+        bool ok[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ok[k] = tile_col(t.vec, lane, k) < t.ncols;
+        float cs[4] = {0.f, 0.f, 0.f, 0.f}, psum = 0.f;
+        float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
+        auto consume = [&](const float x[4]) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                cs[k] += x[k];
+                if (ok[k]) {
+                    atomicAdd(&h[(__builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu) >> 20], 1u);
+                    if (want_p) psum += __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                }
+            }
+            return wave_sum((x[0] + x[1]) + (x[2] + x[3]));
+        };
+        uint32_t r = t.row0;
+        for (; r + 4 <= t.row1; r += 4) {                       // four rows in flight
+            float x[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float rs = consume(x[q]);
+                if (lane == 0) rp[(uint64_t)q * m.n_tiles] = rs;
+            }
+            row += (uint64_t)4 * m.cols; rp += (uint64_t)4 * m.n_tiles;
+        }
+        for (; r < t.row1; ++r) {
+            float x[4];
+            load_tile_row(row, t.vec, lane, t.ncols, x);
+            const float rs = consume(x);
+            if (lane == 0) *rp = rs;
+            row += m.cols; rp += m.n_tiles;
+        }
+        float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (ok[k]) cp[tile_col(t.vec, lane, k)] = cs[k];
+        psum = wave_sum(psum);
+        if (lane == 0) psumpart[t.task] = psum;
+    }
+    __syncthreads();
+    uint32_t* out = hist_all + (uint64_t)m.block * 4 * kBins;
+    for (uint32_t i = threadIdx.x; i < kBins; i += 256)
+        if (h[i]) atomicAdd(&out[i], h[i]);
+}
+
+// r_i, c_j (fp32 for pass 2), mu (fp64) and the block's sum of p from the pass-1 partial sums.
+__global__ __launch_bounds__(256) void k_tile_finish1(const MatRow* __restrict__ mats, const float* __restrict__ rowpart,
+                                                      const float* __restrict__ colpart, const float* __restrict__ psumpart,
+                                                      float* __restrict__ rvec, float* __restrict__ cvec,
+                                                      double* __restrict__ mu_out, double* __restrict__ rec_all)
 {
     const MatRow m = mats[blockIdx.x];
-    double local = 0.0;
+    double local = 0.0, lp = 0.0;
     for (uint32_t i = threadIdx.x; i < m.rows; i += 256) {
         const float* rp = rowpart + m.off_rowpart + (uint64_t)i * m.n_tiles;
         double s = 0.0;
@@ -594,106 +699,155 @@ __global__ __launch_bounds__(256) void k_rowcol_finish(const MatRow* __restrict_
         for (uint32_t g = 0; g < m.n_segs; ++g) s += (double)cp[(uint64_t)g * m.cols];
         cvec[m.off_c + j] = (float)(s / (double)m.rows);
     }
-    __shared__ double sh[256];
-    sh[threadIdx.x] = local;
+    const uint32_t n_tasks = m.n_tiles * m.n_segs;
+    for (uint32_t i = threadIdx.x; i < n_tasks; i += 256) lp += (double)psumpart[m.first_task + i];
+    __shared__ double sh[256], sp[256];
+    sh[threadIdx.x] = local; sp[threadIdx.x] = lp;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        if ((int)threadIdx.x < w) { sh[threadIdx.x] += sh[threadIdx.x + w]; sp[threadIdx.x] += sp[threadIdx.x + w]; }
         __syncthreads();
     }
-    if (threadIdx.x == 0) mu_out[blockIdx.x] = sh[0] / (double)m.rows;
+    if (threadIdx.x == 0) {
+        mu_out[blockIdx.x] = sh[0] / (double)m.rows;
+        rec_all[(uint64_t)m.block * kRecDoubles + R_PSUM] = sp[0];
+    }
 }
 
-__global__ __launch_bounds__(256) void k_resid(const float* __restrict__ v_all, const MatRow* __restrict__ mats,
-                                               uint32_t n_mats, uint32_t n_tasks, const float* __restrict__ rvec,
-                                               const float* __restrict__ cvec, const double* __restrict__ mu_all,
-                                               float* __restrict__ residpart)
+template <int TT>
+__global__ __launch_bounds__(256) void k_tile_pass2(
+    const float* __restrict__ v_all, const typename GradIO<TT>::elem* __restrict__ theta,
+    const MatRow* __restrict__ mats, uint32_t n_mats,
+    const float* __restrict__ rvec, const float* __restrict__ cvec, const double* __restrict__ mu_all,
+    const double* __restrict__ rec_all, const uint32_t* __restrict__ sel_prefix,
+    float* __restrict__ residpart, uint32_t* __restrict__ hist_all, float eps, bool want_F, bool want_C)
 {
-    const uint32_t lane = threadIdx.x & 63u, task = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (task >= n_tasks) return;
-    const MatTask t = decode_task(mats, n_mats, task);
+    typedef GradIO<TT> IO;
+    __shared__ uint32_t h[4 * kBins];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    for (uint32_t i = threadIdx.x; i < 4 * kBins; i += 256) h[i] = 0;
+    const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
     const MatRow& m = mats[t.mat];
-    const double mu = mu_all[t.mat];
-    const float inv_mu = mu != 0.0 ? (float)(1.0 / mu) : 0.f;        // S~ = 0 when mu = 0
-    float cm[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t c = tile_col(t.vec, lane, k);
-        cm[k] = c < t.ncols ? cvec[m.off_c + t.col0 + c] * inv_mu : 0.f;
-    }
-    const float* row = v_all + m.state_start + (uint64_t)t.row0 * m.cols + t.col0;
-    const float* rr = rvec + m.off_r + t.row0;
-    float res = 0.f, s2 = 0.f;
-    uint32_t r = t.row0;
-    for (; r + 4 <= t.row1; r += 4) {
-        float x[4][4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float ri = rr[q];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float d = x[q][k] - ri * cm[k];
-                res = __builtin_fmaf(d, d, res);
-                s2 = __builtin_fmaf(x[q][k], x[q][k], s2);
-            }
-        }
-        row += (uint64_t)4 * m.cols; rr += 4;
-    }
-    for (; r < t.row1; ++r) {
-        float x[4];
-        load_tile_row(row, t.vec, lane, t.ncols, x);
-        const float ri = *rr;
+    const Prefixes d = distinct_prefixes(sel_prefix, m.block);
+    __syncthreads();
+    if (t.valid) {
+        const double mu = mu_all[t.mat];
+        const float inv_mu = mu != 0.0 ? (float)(1.0 / mu) : 0.f;        // S~ = 0 when mu = 0
+        float inv_pbar = 0.f;
+        if (want_C) inv_pbar = (float)((double)((uint64_t)m.rows * m.cols) / rec_all[(uint64_t)m.block * kRecDoubles + R_PSUM]);
+        bool ok[4]; float cm[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float d = x[k] - ri * cm[k];
-            res = __builtin_fmaf(d, d, res);
-            s2 = __builtin_fmaf(x[k], x[k], s2);
+            const uint32_t c = tile_col(t.vec, lane, k);
+            ok[k] = c < t.ncols;
+            cm[k] = ok[k] ? cvec[m.off_c + t.col0 + c] * inv_mu : 0.f;
         }
-        row += m.cols; ++rr;
+        const uint64_t first = (uint64_t)t.row0 * m.cols + t.col0;
+        const float* row = v_all + m.state_start + first;
+        const typename IO::elem* trow = theta + m.grad_start + first;
+        const bool talign = (reinterpret_cast<uintptr_t>(trow) & IO::kAlignMask) == 0;   // cols % 4 == 0: same for all rows
+        const float* rr = rvec + m.off_r + t.row0;
+        float res = 0.f, s2 = 0.f, cn = 0.f, cd = 0.f;
+        auto consume = [&](const float x[4], const float th[4], float ri) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (!ok[k]) continue;
+                const uint32_t key = __builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu;
+                const uint32_t hi = key >> 20, bin = (key >> 9) & 0x7ffu;
+                count_match(h, d, kBins, hi, bin);
+                if (want_F) {
+                    const float d = x[k] - ri * cm[k];
+                    res = __builtin_fmaf(d, d, res);
+                    s2 = __builtin_fmaf(x[k], x[k], s2);
+                }
+                if (want_C) {
+                    const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                    const float y = (p * inv_pbar - 1.0f) * th[k];
+                    cn = __builtin_fmaf(y, y, cn);
+                    cd = __builtin_fmaf(th[k], th[k], cd);
+                }
+            }
+        };
+        uint32_t r = t.row0;
+        for (; r + 4 <= t.row1; r += 4) {
+            float x[4][4], th[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+                if (want_C) load_tile_theta<TT>(trow + (uint64_t)q * m.cols, t.vec, talign, lane, t.ncols, th[q]);
+                else th[q][0] = th[q][1] = th[q][2] = th[q][3] = 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) consume(x[q], th[q], rr[q]);
+            row += (uint64_t)4 * m.cols; trow += (uint64_t)4 * m.cols; rr += 4;
+        }
+        for (; r < t.row1; ++r) {
+            float x[4], th[4] = {0.f, 0.f, 0.f, 0.f};
+            load_tile_row(row, t.vec, lane, t.ncols, x);
+            if (want_C) load_tile_theta<TT>(trow, t.vec, talign, lane, t.ncols, th);
+            consume(x, th, *rr);
+            row += m.cols; trow += m.cols; ++rr;
+        }
+        res = wave_sum(res); s2 = wave_sum(s2); cn = wave_sum(cn); cd = wave_sum(cd);
+        if (lane == 0) {
+            float* o = residpart + (uint64_t)t.task * 4;
+            o[0] = res; o[1] = s2; o[2] = cn; o[3] = cd;
+        }
     }
-    res = wave_sum(res); s2 = wave_sum(s2);
-    if (lane == 0) { residpart[(uint64_t)task * 2] = res; residpart[(uint64_t)task * 2 + 1] = s2; }
+    __syncthreads();
+    uint32_t* out = hist_all + (uint64_t)m.block * 4 * kBins;
+    for (uint32_t i = threadIdx.x; i < kBins; i += 256) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t c = h[d.slot_of[q] * kBins + i];
+            if (c) atomicAdd(&out[q * kBins + i], c);
+        }
+    }
 }
 
-__global__ __launch_bounds__(256) void k_resid_finish(const MatRow* __restrict__ mats, const float* __restrict__ residpart,
+__global__ __launch_bounds__(256) void k_tile_finish2(const MatRow* __restrict__ mats, const float* __restrict__ residpart,
                                                       double* __restrict__ rec_all)
 {
     const MatRow m = mats[blockIdx.x];
     const uint32_t n = m.n_tiles * m.n_segs;
-    double a = 0.0, b = 0.0;
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
     for (uint32_t i = threadIdx.x; i < n; i += 256) {
-        a += (double)residpart[(uint64_t)(m.first_task + i) * 2];
-        b += (double)residpart[(uint64_t)(m.first_task + i) * 2 + 1];
+        const f4 t = *reinterpret_cast<const f4*>(residpart + (uint64_t)(m.first_task + i) * 4);
+        a[0] += (double)t.x; a[1] += (double)t.y; a[2] += (double)t.z; a[3] += (double)t.w;
     }
-    __shared__ double sa[256], sb[256];
-    sa[threadIdx.x] = a; sb[threadIdx.x] = b;
+    __shared__ double sh[4][256];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) sh[q][threadIdx.x] = a[q];
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) { sa[threadIdx.x] += sa[threadIdx.x + w]; sb[threadIdx.x] += sb[threadIdx.x + w]; }
+        if ((int)threadIdx.x < w) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sh[q][threadIdx.x] += sh[q][threadIdx.x + w];
+        }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
         double* rec = rec_all + (uint64_t)m.block * kRecDoubles;
-        rec[R_FRES] = sa[0]; rec[R_FS2] = sb[0];
+        rec[R_FRES] = sh[0][0]; rec[R_FS2] = sh[1][0]; rec[R_CNUM] = sh[2][0]; rec[R_CDEN] = sh[3][0];
     }
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 6: distortion C.  p = 1/(sqrt(v) + eps).  Pass 1: sum of p per chunk (-> p-bar per
-// block).  Pass 2: sum of ((p/p-bar - 1) theta)^2 and of theta^2 per chunk.  theta is laid
-// out like the gradient buffer.  Partial rows reuse the step's partial-sum buffer.
+// Eq. 6 on the chunks of blocks without a matrix shape.  p = 1/(sqrt(v) + eps).
+// Pass 1: sum of p per chunk (-> p-bar per block).  Pass 2: sum of
+// ((p/p-bar - 1) theta)^2 and of theta^2 per chunk.  theta is laid out like the
+// gradient buffer.  Partial rows reuse the step's partial-sum buffer.
 // ---------------------------------------------------------------------------
 
 template <int TT, int PASS>
 __global__ __launch_bounds__(256) void k_distortion(
     const float* __restrict__ v_all, const typename GradIO<TT>::elem* __restrict__ theta,
-    const Chunk* __restrict__ chunks, const BlockRow* __restrict__ rows, const double* __restrict__ rec_all,
-    float* __restrict__ partials, float eps)
+    const Chunk* __restrict__ chunks, const uint32_t* __restrict__ list, const BlockRow* __restrict__ rows,
+    const double* __restrict__ rec_all, float* __restrict__ partials, float eps)
 {
     typedef GradIO<TT> IO;
-    const Chunk ck = chunks[blockIdx.x];
+    const uint32_t cid = list[blockIdx.x];
+    const Chunk ck = chunks[cid];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const typename IO::elem* tsrc = theta + ck.grad_start;
     const bool vec_ok = (reinterpret_cast<uintptr_t>(tsrc) & IO::kAlignMask) == 0;
@@ -729,15 +883,16 @@ __global__ __launch_bounds__(256) void k_distortion(
     if (lane == 0) { red[wave][0] = a0; red[wave][1] = a1; }
     __syncthreads();
     if (threadIdx.x < 2)
-        partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] =
+        partials[(uint64_t)cid * kNumSums + threadIdx.x] =
             (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
-// Per block: fp64 sum of the first `ncols` entries of its partial rows into rec[dst .. dst+ncols).
+// Per chunk-walked block: fp64 sum of the first `ncols` entries of its partial rows into rec[dst .. dst+ncols).
 __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partials, const BlockRow* __restrict__ rows,
                                                          double* __restrict__ rec_all, uint32_t ncols, uint32_t dst)
 {
     const BlockRow br = rows[blockIdx.x];
+    if (br.vec_first == kNoVec) return;                      // tiled block: its sums come from k_tile_finish*
     __shared__ double sh[256];
     for (uint32_t col = 0; col < ncols; ++col) {
         double a = 0.0;
@@ -765,8 +920,9 @@ struct Plan {
     uint64_t n_chunks = 0;
     std::vector<BlockRow> rows;
     std::vector<MatRow> mats;     // matrix blocks (rows*cols == numel), for Eq. 7
-    uint64_t n_tasks = 0;
-    uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0;
+    uint64_t n_tasks = 0, n_quads = 0, n_vec_chunks = 0;
+    uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0,
+             off_psumpart = 0, off_veclist = 0;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
     uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
              off_rec = 0, off_hist = 0, off_selp = 0, off_selr = 0, off_ostat = 0, total = 0;
@@ -833,7 +989,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         r.grad_start = b.offset; r.state_start = state; r.numel = b.numel;
         r.first_chunk = (uint32_t)P.n_chunks;
         r.n_chunks = (uint32_t)((groups + per - 1) / per);
-        r.groups_per_chunk = (uint32_t)per; r.pad_ = 0;
+        r.groups_per_chunk = (uint32_t)per; r.vec_first = 0;
         P.n_chunks += r.n_chunks;
         for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
             const double pos = (q == 0 ? 0.1 : 0.9) * (double)(b.numel - 1);
@@ -845,21 +1001,28 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         if (P.n_chunks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
     }
     P.padded = state;
-    // tiles of the matrix blocks (Eq. 7)
-    P.mats.clear(); P.n_tasks = 0;
+    // Finalize walks blocks with a real matrix shape tile-wise and the rest chunk-wise.  A shape with a
+    // single row or column is rank one by construction (F = 0 exactly) and stays on the chunk path.
+    P.mats.clear(); P.n_tasks = 0; P.n_quads = 0; P.n_vec_chunks = 0;
     uint64_t n_r = 0, n_c = 0, n_rowpart = 0, n_colpart = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const baoc_block& b = blocks[i];
-        if (!b.rows || !b.cols) continue;
+        if (b.rows < 2 || b.cols < 2) {
+            P.rows[i].vec_first = (uint32_t)P.n_vec_chunks;
+            P.n_vec_chunks += P.rows[i].n_chunks;
+            continue;
+        }
+        P.rows[i].vec_first = kNoVec;
         MatRow m;
-        m.state_start = P.rows[i].state_start;
+        m.state_start = P.rows[i].state_start; m.grad_start = b.offset;
         m.rows = b.rows; m.cols = b.cols;
         m.n_tiles = (b.cols + kTileCols - 1) / kTileCols; m.n_segs = (b.rows + kTileRows - 1) / kTileRows;
         m.off_r = n_r; m.off_c = n_c; m.off_rowpart = n_rowpart; m.off_colpart = n_colpart;
-        m.first_task = (uint32_t)P.n_tasks; m.block = i;
+        m.first_task = (uint32_t)P.n_tasks; m.first_quad = (uint32_t)P.n_quads; m.block = i; m.pad_ = 0;
         n_r += b.rows; n_c += b.cols;
         n_rowpart += (uint64_t)b.rows * m.n_tiles; n_colpart += (uint64_t)m.n_segs * b.cols;
-        P.n_tasks += (uint64_t)m.n_tiles * m.n_segs;
+        const uint64_t tasks = (uint64_t)m.n_tiles * m.n_segs;
+        P.n_tasks += tasks; P.n_quads += (tasks + 3) / 4;
         if (P.n_tasks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
         P.mats.push_back(m);
     }
@@ -882,7 +1045,9 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_cvec = o;     o = align_up(o + n_c * 4, 256);
     P.off_rowpart = o;  o = align_up(o + n_rowpart * 4, 256);
     P.off_colpart = o;  o = align_up(o + n_colpart * 4, 256);
-    P.off_residpart = o; o = align_up(o + P.n_tasks * 2 * 4, 256);
+    P.off_residpart = o; o = align_up(o + P.n_tasks * 4 * 4, 256);
+    P.off_psumpart = o; o = align_up(o + P.n_tasks * 4, 256);
+    P.off_veclist = o;  o = align_up(o + P.n_vec_chunks * 4, 256);
     P.total = o;
     return BAOC_OK;
 }
@@ -928,7 +1093,8 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     if (e == hipSuccess) {
         hipLaunchKernelGGL(k_build_chunks, dim3((uint32_t)((P.n_chunks + 255) / 256)), dim3(256), 0, nullptr,
                            reinterpret_cast<const BlockRow*>(h->ws + P.off_rows), n_blocks,
-                           reinterpret_cast<Chunk*>(h->ws + P.off_chunks), (uint32_t)P.n_chunks);
+                           reinterpret_cast<Chunk*>(h->ws + P.off_chunks), (uint32_t)P.n_chunks,
+                           reinterpret_cast<uint32_t*>(h->ws + P.off_veclist));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -995,59 +1161,70 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
 
     const Plan& P = h->plan;
     const uint32_t N = (uint32_t)P.rows.size(), nch = (uint32_t)P.n_chunks;
+    const uint32_t n_vec = (uint32_t)P.n_vec_chunks, n_mats = (uint32_t)P.mats.size(), n_quads = (uint32_t)P.n_quads;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const float* v = reinterpret_cast<const float*>(h->ws + P.off_v);
     const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
     const BlockRow* rows = reinterpret_cast<const BlockRow*>(h->ws + P.off_rows);
+    const uint32_t* vec_list = reinterpret_cast<const uint32_t*>(h->ws + P.off_veclist);
+    const MatRow* mats = reinterpret_cast<const MatRow*>(h->ws + P.off_mats);
     uint32_t* hist = reinterpret_cast<uint32_t*>(h->ws + P.off_hist);
     uint32_t* selp = reinterpret_cast<uint32_t*>(h->ws + P.off_selp);
     uint32_t* selr = reinterpret_cast<uint32_t*>(h->ws + P.off_selr);
     float* ostat = reinterpret_cast<float*>(h->ws + P.off_ostat);
+    float* rvec = reinterpret_cast<float*>(h->ws + P.off_rvec);
+    float* cvec = reinterpret_cast<float*>(h->ws + P.off_cvec);
+    float* rowpart = reinterpret_cast<float*>(h->ws + P.off_rowpart);
+    float* colpart = reinterpret_cast<float*>(h->ws + P.off_colpart);
+    float* residpart = reinterpret_cast<float*>(h->ws + P.off_residpart);
+    float* psumpart = reinterpret_cast<float*>(h->ws + P.off_psumpart);
+    double* mu = reinterpret_cast<double*>(h->ws + P.off_mu);
+    float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
+    double* rec = reinterpret_cast<double*>(h->ws + P.off_rec);
+    const float epsf = (float)h->params.eps;
+    const bool th32 = rp.theta_dtype == BAOC_GRAD_F32;
+    const float* th_f = static_cast<const float*>(rp.d_theta_flat);
+    const uint16_t* th_h = static_cast<const uint16_t*>(rp.d_theta_flat);
     const uint64_t hist_words = (uint64_t)N * 4 * kBins;
     const uint32_t fill_grid = (uint32_t)std::min<uint64_t>((hist_words + 255) / 256, 4096);
-    const uint32_t hist_grid = std::min(nch, kHistGrid);
 
+    // pass 1 over v: first digit everywhere; row/column sums and the sum of p on the way
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<1>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
-    hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
-    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<2>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
-    hipLaunchKernelGGL(k_pick<2>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
-    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<3>, dim3(hist_grid), dim3(256), 0, st, v, ch, nch, selp, hist);
-    hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
-
-    if (want_F) {
-        const MatRow* mats = reinterpret_cast<const MatRow*>(h->ws + P.off_mats);
-        const uint32_t n_mats = (uint32_t)P.mats.size(), n_tasks = (uint32_t)P.n_tasks;
-        float* rvec = reinterpret_cast<float*>(h->ws + P.off_rvec);
-        float* cvec = reinterpret_cast<float*>(h->ws + P.off_cvec);
-        float* rowpart = reinterpret_cast<float*>(h->ws + P.off_rowpart);
-        float* colpart = reinterpret_cast<float*>(h->ws + P.off_colpart);
-        float* residpart = reinterpret_cast<float*>(h->ws + P.off_residpart);
-        double* mu = reinterpret_cast<double*>(h->ws + P.off_mu);
-        hipLaunchKernelGGL(k_rowcol, dim3((n_tasks + 3) / 4), dim3(256), 0, st, v, mats, n_mats, n_tasks, rowpart, colpart);
-        hipLaunchKernelGGL(k_rowcol_finish, dim3(n_mats), dim3(256), 0, st, mats, rowpart, colpart, rvec, cvec, mu);
-        hipLaunchKernelGGL(k_resid, dim3((n_tasks + 3) / 4), dim3(256), 0, st, v, mats, n_mats, n_tasks, rvec, cvec, mu, residpart);
-        hipLaunchKernelGGL(k_resid_finish, dim3(n_mats), dim3(256), 0, st, mats, residpart, reinterpret_cast<double*>(h->ws + P.off_rec));
-    }
-    if (want_C) {
-        float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
-        double* rec = reinterpret_cast<double*>(h->ws + P.off_rec);
-        const float epsf = (float)h->params.eps;
-        if (rp.theta_dtype == BAOC_GRAD_F32) {
-            const float* th = static_cast<const float*>(rp.d_theta_flat);
-            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 1>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
+    if (n_quads)
+        hipLaunchKernelGGL(k_tile_pass1, dim3(n_quads), dim3(256), 0, st, v, mats, n_mats, rowpart, colpart, psumpart, hist, epsf, want_C);
+    if (n_vec) {
+        hipLaunchKernelGGL(k_hist<1>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist);
+        if (want_C) {
+            if (th32) hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 1>), dim3(n_vec), dim3(256), 0, st, v, th_f, ch, vec_list, rows, rec, part, epsf);
+            else hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 1>), dim3(n_vec), dim3(256), 0, st, v, th_h, ch, vec_list, rows, rec, part, epsf);
             hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 1u, (uint32_t)R_PSUM);
-            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 2>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
-        } else {
-            const uint16_t* th = static_cast<const uint16_t*>(rp.d_theta_flat);
-            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 1>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
-            hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 1u, (uint32_t)R_PSUM);
-            hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 2>), dim3(nch), dim3(256), 0, st, v, th, ch, rows, rec, part, epsf);
         }
-        hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 2u, (uint32_t)R_CNUM);
     }
+    if (n_quads)
+        hipLaunchKernelGGL(k_tile_finish1, dim3(n_mats), dim3(256), 0, st, mats, rowpart, colpart, psumpart, rvec, cvec, mu, rec);
+    hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
+
+    // pass 2 over v (and theta): second digit; rank-1 residual and distortion on the way
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
+    if (n_quads) {
+        if (th32) hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_F32>, dim3(n_quads), dim3(256), 0, st, v, th_f, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, epsf, want_F, want_C);
+        else hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_BF16>, dim3(n_quads), dim3(256), 0, st, v, th_h, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, epsf, want_F, want_C);
+        hipLaunchKernelGGL(k_tile_finish2, dim3(n_mats), dim3(256), 0, st, mats, residpart, rec);
+    }
+    if (n_vec) {
+        hipLaunchKernelGGL(k_hist<2>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist);
+        if (want_C) {
+            if (th32) hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 2>), dim3(n_vec), dim3(256), 0, st, v, th_f, ch, vec_list, rows, rec, part, epsf);
+            else hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 2>), dim3(n_vec), dim3(256), 0, st, v, th_h, ch, vec_list, rows, rec, part, epsf);
+            hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 2u, (uint32_t)R_CNUM);
+        }
+    }
+    hipLaunchKernelGGL(k_pick<2>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
+
+    // pass 3 over v: last digit, chunk-wise for every block
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
+    hipLaunchKernelGGL(k_hist<3>, dim3(std::min(nch, kHistGrid)), dim3(256), 0, st, v, ch, static_cast<const uint32_t*>(nullptr), nch, selp, hist);
+    hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
 
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h->h_rec.data(), h->ws + P.off_rec, h->h_rec.size() * 8, hipMemcpyDeviceToHost, st);
@@ -1069,7 +1246,7 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
         const double eps = h->params.eps;
         double C_raw = rp.C_raw ? rp.C_raw[i] : 0.0, F_raw = rp.F_raw ? rp.F_raw[i] : 0.0;
         if (want_C) C_raw = std::sqrt(rec[R_CNUM]) / (std::sqrt(rec[R_CDEN]) + eps);                  // Eq. 6
-        if (want_F && h->blocks[i].rows) F_raw = std::sqrt(rec[R_FRES]) / (std::sqrt(rec[R_FS2]) + eps);   // Eq. 7
+        if (want_F && P.rows[i].vec_first == kNoVec) F_raw = std::sqrt(rec[R_FRES]) / (std::sqrt(rec[R_FS2]) + eps);   // Eq. 7
         block_metrics(r, eps, rp, C_raw, F_raw, &stats[i]);
     }
     if (out_stats) std::memcpy(out_stats, stats.data(), sizeof(baoc_block_stats) * N);
