@@ -129,11 +129,10 @@ template <int GT> struct GradIO;
 
 template <> struct GradIO<BAOC_GRAD_F32> {
     typedef float elem;
-    __device__ static __forceinline__ void load4(const elem* p, float g[4])
-    {
-        f4 t = ld_stream<f4>(p);
-        g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w;
-    }
+    typedef f4 vec4;                                      // four elements as loaded
+    __device__ static __forceinline__ vec4 loadv(const elem* p) { return ld_stream<f4>(p); }
+    __device__ static __forceinline__ void unpack(vec4 t, float g[4]) { g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w; }
+    __device__ static __forceinline__ void load4(const elem* p, float g[4]) { unpack(loadv(p), g); }
     __device__ static __forceinline__ float load1(const elem* p) { return *p; }
     __device__ static __forceinline__ void store4(elem* p, const float g[4])
     {
@@ -145,12 +144,14 @@ template <> struct GradIO<BAOC_GRAD_F32> {
 
 template <> struct GradIO<BAOC_GRAD_BF16> {
     typedef uint16_t elem;
-    __device__ static __forceinline__ void load4(const elem* p, float g[4])
+    typedef u2 vec4;
+    __device__ static __forceinline__ vec4 loadv(const elem* p) { return ld_stream<u2>(p); }
+    __device__ static __forceinline__ void unpack(vec4 t, float g[4])
     {
-        u2 t = ld_stream<u2>(p);
         g[0] = __builtin_bit_cast(float, t.x << 16); g[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
         g[2] = __builtin_bit_cast(float, t.y << 16); g[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
     }
+    __device__ static __forceinline__ void load4(const elem* p, float g[4]) { unpack(loadv(p), g); }
     __device__ static __forceinline__ float load1(const elem* p) { return bf16_widen(*p); }
     // g holds exact bf16 values: the upper half of each word is the stored pattern
     __device__ static __forceinline__ void store4(elem* p, const float g[4])
@@ -186,25 +187,41 @@ __global__ __launch_bounds__(256) void k_step(
 #pragma unroll
     for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.f;
 
+    // The loads of a group are issued one iteration ahead of their use, so a wavefront always has
+    // the next 22/28 bytes per coordinate in flight while it works on the current ones.
+    typedef typename IO::vec4 GV;
+    f4 nm = {0.f, 0.f, 0.f, 0.f}, nv = {0.f, 0.f, 0.f, 0.f};
+    GV np = {}, ng = {};
+    auto issue = [&](uint32_t grp) {
+        const uint32_t e = grp * kQB + lane * 4;
+        const uint64_t si = ck.state_start + e;           // states are padded to whole groups
+        if (!FIRST) { nm = ld_stream<f4>(m_all + si); nv = ld_stream<f4>(v_all + si); np = IO::loadv(gp_all + si); }
+        if (vec_ok && e + 4 <= ck.count) ng = IO::loadv(gsrc + e);
+    };
+    if (wave < ngroups) issue(wave);
+
     for (uint32_t grp = wave; grp < ngroups; grp += 4) {
         const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
-        const uint64_t si = ck.state_start + e;           // states are padded to whole groups
+        const uint64_t si = ck.state_start + e;
         float g[4], p[4], m[4], v[4];
-        if (FIRST) {
+        {
+            const f4 cm = nm, cv = nv;
+            const GV cp = np, cg = ng;
+            if (grp + 4 < ngroups) issue(grp + 4);
+            if (FIRST) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
-        } else {
-            f4 t = ld_stream<f4>(m_all + si);
-            m[0] = t.x; m[1] = t.y; m[2] = t.z; m[3] = t.w;
-            t = ld_stream<f4>(v_all + si);
-            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-            IO::load4(gp_all + si, p);
-        }
-        if (vec_ok && e + 4 <= ck.count) {
-            IO::load4(gsrc + e, g);
-        } else {                                          // ragged tail or unaligned block start
+                for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
+            } else {
+                m[0] = cm.x; m[1] = cm.y; m[2] = cm.z; m[3] = cm.w;
+                v[0] = cv.x; v[1] = cv.y; v[2] = cv.z; v[3] = cv.w;
+                IO::unpack(cp, p);
+            }
+            if (vec_ok && e + 4 <= ck.count) {
+                IO::unpack(cg, g);
+            } else {                                      // ragged tail or unaligned block start
 #pragma unroll
-            for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
+                for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
+            }
         }
 
         // Eq. 3 in fp32: the new term is rounded, then one fused multiply-add
