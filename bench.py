@@ -168,7 +168,7 @@ def main():
         "config": {"workload": f"{w.name}: {len(w.blocks)} blocks, {D:,} coordinates, {w.grad_dtype} gradients, "
                                f"fp32 EMA states, window of {K} steps + finalize + allocate (K={len(w.configs)} configurations)",
                    "blocks": len(w.blocks), "coordinates": D, "grad_dtype": w.grad_dtype, "window_steps": K,
-                   "gradient_ring": R, "workspace_bytes": nbytes, "chunk_groups": a.chunk_groups or 16},
+                   "gradient_ring": R, "workspace_bytes": nbytes, "chunk_groups": a.chunk_groups or 4},
         "breakdown_ms": {"begin": round(r["begin"] * 1e3, 3), "first_step": round(step_ms[0], 4), "step_avg": round(avg_ms, 4),
                          "step_min": round(min(steady), 4), "finalize": round(finalize_ms, 3),
                          "allocate": round(r["allocate"] * 1e3, 3)},

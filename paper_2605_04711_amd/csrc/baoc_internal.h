@@ -9,7 +9,7 @@ namespace baoc {
 
 constexpr uint32_t kQB = 256;            // coordinates per 8-bit absmax group = one wavefront x 4
 constexpr uint32_t kNumSums = 16;        // floats in one partial-sum row
-constexpr uint32_t kDefaultChunkGroups = 16;
+constexpr uint32_t kDefaultChunkGroups = 4;    // one group per wavefront: no wavefront waits on its own stores
 
 // order of the sums in a partial row and in the per-block raw record
 enum Sum : int {

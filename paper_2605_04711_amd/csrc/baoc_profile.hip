@@ -42,6 +42,7 @@ struct alignas(8) BlockRow {
     uint32_t first_chunk, n_chunks;
     uint32_t groups_per_chunk;
     uint32_t vec_first;     // first entry of the block in the list of chunks finalize walks chunk-wise; kNoVec when tiled
+    uint32_t first_slab, n_slabs;   // the block's slabs of partial rows (first stage of the per-block sum)
     uint64_t rank[4];       // order statistics wanted from v: lo(0.1), lo+1, lo(0.9), lo+1
 };
 
@@ -77,6 +78,16 @@ __device__ __forceinline__ float wave_max(float x)
     x = fmaxf(x, dpp<0x142, 0xa>(x, x));
     x = fmaxf(x, dpp<0x143, 0xc>(x, x));
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// sum over each row of 16 lanes, left in every lane of the row
+__device__ __forceinline__ float row_sum(float x)
+{
+    x += dpp<0xB1, 0xf>(0.f, x);
+    x += dpp<0x4E, 0xf>(0.f, x);
+    x += dpp<0x124, 0xf>(0.f, x);
+    x += dpp<0x128, 0xf>(0.f, x);
+    return x;
 }
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -203,6 +214,8 @@ __global__ __launch_bounds__(256) void k_step(
     for (uint32_t grp = wave; grp < ngroups; grp += 4) {
         const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
         const uint64_t si = ck.state_start + e;
+        float* m_dst = m_all + si;                        // store addresses formed early: the stores then
+        float* v_dst = v_all + si;                        // leave as soon as the updated states exist
         float g[4], p[4], m[4], v[4];
         {
             const f4 cm = nm, cv = nv;
@@ -234,9 +247,9 @@ __global__ __launch_bounds__(256) void k_step(
         }
         {
             f4 t = {m[0], m[1], m[2], m[3]};
-            st_stream<f4>(m_all + si, t);
+            st_stream<f4>(m_dst, t);
             f4 s = {v[0], v[1], v[2], v[3]};
-            st_stream<f4>(v_all + si, s);
+            st_stream<f4>(v_dst, s);
         }
         IO::store4(gp_all + si, g);
 
@@ -285,16 +298,19 @@ __global__ __launch_bounds__(256) void k_step(
         }
     }
 
-    // wavefront -> LDS -> one partial row per chunk, in a fixed order
-    __shared__ float red[4][kNumSums];
+    // DPP inside each row of 16 lanes -> LDS (4 wavefronts x 4 rows) -> one partial row per chunk,
+    // in a fixed order
+    __shared__ float red[16][kNumSums];
 #pragma unroll
     for (int i = 0; i < (int)kNumSums; ++i) {
-        const float s = wave_sum(acc[i]);
-        if (lane == 0) red[wave][i] = s;
+        const float s = row_sum(acc[i]);
+        if ((lane & 15u) == 0) red[wave * 4 + (lane >> 4)][i] = s;
     }
     __syncthreads();
     if (threadIdx.x < kNumSums) {
-        const float s = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s += red[q][threadIdx.x];
         partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] = s;
     }
 }
@@ -303,16 +319,20 @@ __global__ __launch_bounds__(256) void k_step(
 // then folds the step into the running direction stability (Eq. 5, left):
 //   cos_t = <g_t,g_{t-1}> / (|g_t| |g_{t-1}| + eps), NaN -> 0 (App. A.1);
 //   the first cosine initialises rho_bar, later ones enter with weight 1 - beta_rho.
-__global__ __launch_bounds__(256) void k_block_reduce(
-    const float* __restrict__ partials, const BlockRow* __restrict__ rows,
-    double* __restrict__ rec_all, uint32_t step, double beta_rho, double eps)
+constexpr uint32_t kSlabRows = 4096;      // partial rows summed by one workgroup of the first stage
+
+struct alignas(8) Slab { uint32_t first_chunk, n_chunks; };
+
+// First stage of the per-block sum: one workgroup adds a slab of partial rows in fp64.
+__global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ partials, const Slab* __restrict__ slabs,
+                                                     double* __restrict__ slab_sums)
 {
-    const BlockRow br = rows[blockIdx.x];
+    const Slab sl = slabs[blockIdx.x];
     double acc[kNumSums];
 #pragma unroll
     for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.0;
-    for (uint32_t c = threadIdx.x; c < br.n_chunks; c += 256) {
-        const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(br.first_chunk + c) * kNumSums);
+    for (uint32_t c = threadIdx.x; c < sl.n_chunks; c += 256) {
+        const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(sl.first_chunk + c) * kNumSums);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const f4 t = row[q];
@@ -321,7 +341,6 @@ __global__ __launch_bounds__(256) void k_block_reduce(
         }
     }
     __shared__ double sh[256];
-    double* rec = rec_all + (uint64_t)blockIdx.x * kRecDoubles;
 #pragma unroll 1
     for (int i = 0; i < (int)kNumSums; ++i) {
         sh[threadIdx.x] = acc[i];
@@ -330,9 +349,23 @@ __global__ __launch_bounds__(256) void k_block_reduce(
             if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
             __syncthreads();
         }
-        if (threadIdx.x == 0) rec[i] = sh[0];
+        if (threadIdx.x == 0) slab_sums[(uint64_t)blockIdx.x * kNumSums + i] = sh[0];
         __syncthreads();
     }
+}
+
+__global__ __launch_bounds__(64) void k_block_reduce(
+    const double* __restrict__ slab_sums, const BlockRow* __restrict__ rows,
+    double* __restrict__ rec_all, uint32_t step, double beta_rho, double eps)
+{
+    const BlockRow br = rows[blockIdx.x];
+    double* rec = rec_all + (uint64_t)blockIdx.x * kRecDoubles;
+    if (threadIdx.x < kNumSums) {
+        double a = 0.0;
+        for (uint32_t t = 0; t < br.n_slabs; ++t) a += slab_sums[(uint64_t)(br.first_slab + t) * kNumSums + threadIdx.x];
+        rec[threadIdx.x] = a;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         const double S_gg = rec[S_GG], S_gp = rec[S_GP];
         if (step >= 2) {
@@ -938,6 +971,8 @@ struct Plan {
     std::vector<BlockRow> rows;
     std::vector<MatRow> mats;     // matrix blocks (rows*cols == numel), for Eq. 7
     uint64_t n_tasks = 0, n_quads = 0, n_vec_chunks = 0;
+    std::vector<Slab> slabs;
+    uint64_t off_slabs = 0, off_slabsums = 0;
     uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0,
              off_psumpart = 0, off_veclist = 0;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
@@ -995,7 +1030,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
 
     const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : kDefaultChunkGroups;
     Plan& P = *out;
-    P.n_chunks = 0; P.rows.resize(n);
+    P.n_chunks = 0; P.rows.resize(n); P.slabs.clear();
     uint64_t state = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const baoc_block& b = blocks[i];
@@ -1007,6 +1042,10 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         r.first_chunk = (uint32_t)P.n_chunks;
         r.n_chunks = (uint32_t)((groups + per - 1) / per);
         r.groups_per_chunk = (uint32_t)per; r.vec_first = 0;
+        r.first_slab = (uint32_t)P.slabs.size();
+        for (uint32_t c = 0; c < r.n_chunks; c += kSlabRows)
+            P.slabs.push_back(Slab{r.first_chunk + c, std::min(kSlabRows, r.n_chunks - c)});
+        r.n_slabs = (uint32_t)P.slabs.size() - r.first_slab;
         P.n_chunks += r.n_chunks;
         for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
             const double pos = (q == 0 ? 0.1 : 0.9) * (double)(b.numel - 1);
@@ -1065,6 +1104,8 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_residpart = o; o = align_up(o + P.n_tasks * 4 * 4, 256);
     P.off_psumpart = o; o = align_up(o + P.n_tasks * 4, 256);
     P.off_veclist = o;  o = align_up(o + P.n_vec_chunks * 4, 256);
+    P.off_slabs = o;    o = align_up(o + P.slabs.size() * sizeof(Slab), 256);
+    P.off_slabsums = o; o = align_up(o + P.slabs.size() * kNumSums * 8, 256);
     P.total = o;
     return BAOC_OK;
 }
@@ -1105,6 +1146,8 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     // (padding included), so only the small tail of the workspace is cleared here.
     hipError_t e = hipMemset(h->ws + P.off_rec, 0, P.off_mats - P.off_rec);
     if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_rows, P.rows.data(), P.rows.size() * sizeof(BlockRow), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(h->ws + P.off_slabs, P.slabs.data(), P.slabs.size() * sizeof(Slab), hipMemcpyHostToDevice);
     if (e == hipSuccess && !P.mats.empty())
         e = hipMemcpy(h->ws + P.off_mats, P.mats.data(), P.mats.size() * sizeof(MatRow), hipMemcpyHostToDevice);
     if (e == hipSuccess) {
@@ -1148,8 +1191,11 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
                            static_cast<const uint16_t*>(d_grad_flat), m, v, reinterpret_cast<hp>(h->ws + P.off_gp), ch, part, k);
     }
     h->steps += 1;
-    hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(256), 0, st,
-                       part, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
+    double* slab_sums = reinterpret_cast<double*>(h->ws + P.off_slabsums);
+    hipLaunchKernelGGL(k_slab_reduce, dim3((uint32_t)P.slabs.size()), dim3(256), 0, st,
+                       part, reinterpret_cast<const Slab*>(h->ws + P.off_slabs), slab_sums);
+    hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(64), 0, st,
+                       slab_sums, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
                        reinterpret_cast<double*>(h->ws + P.off_rec), h->steps, q.beta_rho, q.eps);
     if (hipGetLastError() != hipSuccess) { h->sticky = BAOC_ERR_HIP; return BAOC_ERR_HIP; }
     return BAOC_OK;
