@@ -315,15 +315,13 @@ __global__ __launch_bounds__(256) void k_step(
     }
 }
 
-// Second stage: one workgroup per parameter block adds that block's partial rows in fp64,
-// then folds the step into the running direction stability (Eq. 5, left):
-//   cos_t = <g_t,g_{t-1}> / (|g_t| |g_{t-1}| + eps), NaN -> 0 (App. A.1);
-//   the first cosine initialises rho_bar, later ones enter with weight 1 - beta_rho.
+// Per-block sums of the partial rows, in fp64.  Blocks with more than kSlabRows chunks are summed in
+// two stages (slabs of kSlabRows rows by k_slab_reduce, then k_block_reduce); smaller ones directly.
 constexpr uint32_t kSlabRows = 4096;      // partial rows summed by one workgroup of the first stage
 
 struct alignas(8) Slab { uint32_t first_chunk, n_chunks; };
 
-// First stage of the per-block sum: one workgroup adds a slab of partial rows in fp64.
+// First stage for large blocks: one workgroup adds a slab of partial rows in fp64.
 __global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ partials, const Slab* __restrict__ slabs,
                                                      double* __restrict__ slab_sums)
 {
@@ -354,16 +352,48 @@ __global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ p
     }
 }
 
-__global__ __launch_bounds__(64) void k_block_reduce(
-    const double* __restrict__ slab_sums, const BlockRow* __restrict__ rows,
+// Second stage, one workgroup per parameter block: the block's slab sums -- or, for a block of at
+// most one slab (n_slabs == 0), its partial rows directly -- are added in fp64, then the step is
+// folded into the running direction stability (Eq. 5, left):
+//   cos_t = <g_t,g_{t-1}> / (|g_t| |g_{t-1}| + eps), NaN -> 0 (App. A.1);
+//   the first cosine initialises rho_bar, later ones enter with weight 1 - beta_rho.
+__global__ __launch_bounds__(256) void k_block_reduce(
+    const float* __restrict__ partials, const double* __restrict__ slab_sums, const BlockRow* __restrict__ rows,
     double* __restrict__ rec_all, uint32_t step, double beta_rho, double eps)
 {
     const BlockRow br = rows[blockIdx.x];
     double* rec = rec_all + (uint64_t)blockIdx.x * kRecDoubles;
-    if (threadIdx.x < kNumSums) {
-        double a = 0.0;
-        for (uint32_t t = 0; t < br.n_slabs; ++t) a += slab_sums[(uint64_t)(br.first_slab + t) * kNumSums + threadIdx.x];
-        rec[threadIdx.x] = a;
+    if (br.n_slabs) {
+        if (threadIdx.x < kNumSums) {
+            double a = 0.0;
+            for (uint32_t t = 0; t < br.n_slabs; ++t) a += slab_sums[(uint64_t)(br.first_slab + t) * kNumSums + threadIdx.x];
+            rec[threadIdx.x] = a;
+        }
+    } else {
+        double acc[kNumSums];
+#pragma unroll
+        for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.0;
+        for (uint32_t c = threadIdx.x; c < br.n_chunks; c += 256) {
+            const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(br.first_chunk + c) * kNumSums);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4 t = row[q];
+                acc[4 * q + 0] += (double)t.x; acc[4 * q + 1] += (double)t.y;
+                acc[4 * q + 2] += (double)t.z; acc[4 * q + 3] += (double)t.w;
+            }
+        }
+        __shared__ double sh[256];
+#pragma unroll 1
+        for (int i = 0; i < (int)kNumSums; ++i) {
+            sh[threadIdx.x] = acc[i];
+            __syncthreads();
+            for (int w = 128; w > 0; w >>= 1) {
+                if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+                __syncthreads();
+            }
+            if (threadIdx.x == 0) rec[i] = sh[0];
+            __syncthreads();
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -1043,8 +1073,9 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         r.n_chunks = (uint32_t)((groups + per - 1) / per);
         r.groups_per_chunk = (uint32_t)per; r.vec_first = 0;
         r.first_slab = (uint32_t)P.slabs.size();
-        for (uint32_t c = 0; c < r.n_chunks; c += kSlabRows)
-            P.slabs.push_back(Slab{r.first_chunk + c, std::min(kSlabRows, r.n_chunks - c)});
+        if (r.n_chunks > kSlabRows)                                  // small blocks are summed directly
+            for (uint32_t c = 0; c < r.n_chunks; c += kSlabRows)
+                P.slabs.push_back(Slab{r.first_chunk + c, std::min(kSlabRows, r.n_chunks - c)});
         r.n_slabs = (uint32_t)P.slabs.size() - r.first_slab;
         P.n_chunks += r.n_chunks;
         for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
@@ -1146,7 +1177,7 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     // (padding included), so only the small tail of the workspace is cleared here.
     hipError_t e = hipMemset(h->ws + P.off_rec, 0, P.off_mats - P.off_rec);
     if (e == hipSuccess) e = hipMemcpy(h->ws + P.off_rows, P.rows.data(), P.rows.size() * sizeof(BlockRow), hipMemcpyHostToDevice);
-    if (e == hipSuccess)
+    if (e == hipSuccess && !P.slabs.empty())
         e = hipMemcpy(h->ws + P.off_slabs, P.slabs.data(), P.slabs.size() * sizeof(Slab), hipMemcpyHostToDevice);
     if (e == hipSuccess && !P.mats.empty())
         e = hipMemcpy(h->ws + P.off_mats, P.mats.data(), P.mats.size() * sizeof(MatRow), hipMemcpyHostToDevice);
@@ -1192,10 +1223,11 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
     }
     h->steps += 1;
     double* slab_sums = reinterpret_cast<double*>(h->ws + P.off_slabsums);
-    hipLaunchKernelGGL(k_slab_reduce, dim3((uint32_t)P.slabs.size()), dim3(256), 0, st,
-                       part, reinterpret_cast<const Slab*>(h->ws + P.off_slabs), slab_sums);
-    hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(64), 0, st,
-                       slab_sums, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
+    if (!P.slabs.empty())
+        hipLaunchKernelGGL(k_slab_reduce, dim3((uint32_t)P.slabs.size()), dim3(256), 0, st,
+                           part, reinterpret_cast<const Slab*>(h->ws + P.off_slabs), slab_sums);
+    hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(256), 0, st,
+                       part, slab_sums, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
                        reinterpret_cast<double*>(h->ws + P.off_rec), h->steps, q.beta_rho, q.eps);
     if (hipGetLastError() != hipSuccess) { h->sticky = BAOC_ERR_HIP; return BAOC_ERR_HIP; }
     return BAOC_OK;
