@@ -73,3 +73,21 @@ def test_full_size_sampling_of_the_7b_layout(env):  # noqa: F811
         assert np.array_equal(smp.indices(i).cpu().numpy(), want)
         o, n = smp.compact_blocks[i][0], smp.compact_blocks[i][1]
         assert torch.equal(compact[o:o + n], buf[torch.from_numpy(want).cuda()])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_device_gradient_generator_matches_its_host_twin(env, dtype):  # noqa: F811
+    """Same counter-based stream on both sides (float32 transcendental differences aside)."""
+    from synth import gradgen
+    device = env["device"]
+    w = ragged_workload(dtype, 64)
+    w.blocks[2].noise = W.STUDENT_T3
+    buf = device.fill(w, device.new_buffer(w), 9, 4)
+    got = to_host_bits(buf)
+    want = gradgen.flat_gradient(w, 9, 4)
+    if dtype == "bf16":
+        a, b = gradgen.bf16_bits_to_f32(got).astype(np.float64), gradgen.bf16_bits_to_f32(want).astype(np.float64)
+        assert np.all(np.abs(a - b) <= 2.0 ** -7 * np.abs(b) + 1e-12)        # at most one bf16 step apart
+        assert np.mean(got == want) > 0.98
+    else:
+        np.testing.assert_allclose(got, want, rtol=2e-4, atol=1e-9)
