@@ -77,17 +77,25 @@ def test_full_size_sampling_of_the_7b_layout(env):  # noqa: F811
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_device_gradient_generator_matches_its_host_twin(env, dtype):  # noqa: F811
-    """Same counter-based stream on both sides (float32 transcendental differences aside)."""
+    """Same counter-based stream on both sides: the device evaluates the transcendentals in
+    float32, the twin in float64, so blocks agree in norm to ~1e-6 and nearly all bf16 codes match."""
     from synth import gradgen
     device = env["device"]
     w = ragged_workload(dtype, 64)
     w.blocks[2].noise = W.STUDENT_T3
-    buf = device.fill(w, device.new_buffer(w), 9, 4)
-    got = to_host_bits(buf)
+    w.blocks[9].noise = W.STUDENT_T3
+    got = to_host_bits(device.fill(w, device.new_buffer(w), 9, 4))
     want = gradgen.flat_gradient(w, 9, 4)
     if dtype == "bf16":
-        a, b = gradgen.bf16_bits_to_f32(got).astype(np.float64), gradgen.bf16_bits_to_f32(want).astype(np.float64)
-        assert np.all(np.abs(a - b) <= 2.0 ** -7 * np.abs(b) + 1e-12)        # at most one bf16 step apart
         assert np.mean(got == want) > 0.98
-    else:
-        np.testing.assert_allclose(got, want, rtol=2e-4, atol=1e-9)
+        got, want = gradgen.bf16_bits_to_f32(got), gradgen.bf16_bits_to_f32(want)
+    got, want = got.astype(np.float64), want.astype(np.float64)
+    tol = 2.0 ** -7 if dtype == "bf16" else 1e-5
+    for i, b in enumerate(w.blocks):
+        a, r = got[b.offset:b.offset + b.numel], want[b.offset:b.offset + b.numel]
+        assert np.linalg.norm(a - r) <= tol * np.linalg.norm(r), f"block {i}"
+        assert np.max(np.abs(a - r)) <= 10 * tol * np.max(np.abs(r)), f"block {i}"
+    used = np.zeros(w.buffer_numel, bool)
+    for b in w.blocks:
+        used[b.offset:b.offset + b.numel] = True
+    assert not got[~used].any()                                   # gaps between blocks stay zero
