@@ -66,28 +66,30 @@ __device__ __forceinline__ float dpp(float old, float x)
         __builtin_bit_cast(int, old), __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xf, false));
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t old, uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+
 // quad_perm[1,0,3,2]=0xB1, quad_perm[2,3,0,1]=0x4E, row_ror:4=0x124, row_ror:8=0x128 leave every
 // lane of a row with the row's total; row_bcast:15 (0x142, rows 1 and 3) and row_bcast:31
 // (0x143, rows 2 and 3) carry the totals upwards so that lane 63 ends with the wavefront's.
-__device__ __forceinline__ float wave_max(float x)
+//
+// Largest of the lanes' non-negative binary32 values.  Among non-negative values the order of the
+// bit patterns as unsigned integers is the order of the values, so the reduction runs on integers
+// (one v_max_u32 with a DPP operand per level).  A NaN pattern ranks above +inf, so a NaN anywhere
+// in the group comes out as the maximum; such a group's sums are NaN whatever its scale is.
+__device__ __forceinline__ float wave_max_nonneg(float v)
 {
-    x = fmaxf(x, dpp<0xB1, 0xf>(x, x));
-    x = fmaxf(x, dpp<0x4E, 0xf>(x, x));
-    x = fmaxf(x, dpp<0x124, 0xf>(x, x));
-    x = fmaxf(x, dpp<0x128, 0xf>(x, x));
-    x = fmaxf(x, dpp<0x142, 0xa>(x, x));
-    x = fmaxf(x, dpp<0x143, 0xc>(x, x));
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
-}
-
-// sum over each row of 16 lanes, left in every lane of the row
-__device__ __forceinline__ float row_sum(float x)
-{
-    x += dpp<0xB1, 0xf>(0.f, x);
-    x += dpp<0x4E, 0xf>(0.f, x);
-    x += dpp<0x124, 0xf>(0.f, x);
-    x += dpp<0x128, 0xf>(0.f, x);
-    return x;
+    uint32_t x = __builtin_bit_cast(uint32_t, v);
+    x = max(x, dpp_u32<0xB1, 0xf>(0u, x));
+    x = max(x, dpp_u32<0x4E, 0xf>(0u, x));
+    x = max(x, dpp_u32<0x124, 0xf>(0u, x));
+    x = max(x, dpp_u32<0x128, 0xf>(0u, x));
+    x = max(x, dpp_u32<0x142, 0xa>(0u, x));
+    x = max(x, dpp_u32<0x143, 0xc>(0u, x));
+    return __builtin_bit_cast(float, (uint32_t)__builtin_amdgcn_readlane((int)x, 63));
 }
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -254,8 +256,8 @@ __global__ __launch_bounds__(256) void k_step(
         IO::store4(gp_all + si, g);
 
         // group absmax of the 256 coordinates this wavefront holds
-        const float a_m = wave_max(fmaxf(fmaxf(fabsf(m[0]), fabsf(m[1])), fmaxf(fabsf(m[2]), fabsf(m[3]))));
-        const float a_v = wave_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+        const float a_m = wave_max_nonneg(fmaxf(fmaxf(fabsf(m[0]), fabsf(m[1])), fmaxf(fabsf(m[2]), fabsf(m[3]))));
+        const float a_v = wave_max_nonneg(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
         // 8-bit code = rint(x * (L / a)) decided in fp32 with a correctly rounded quotient;
         // an infinite scale (a == 0 or tiny) means all codes are 0
         float s_m = 127.0f / a_m, s_v = 255.0f / a_v;
@@ -298,19 +300,38 @@ __global__ __launch_bounds__(256) void k_step(
         }
     }
 
-    // DPP inside each row of 16 lanes -> LDS (4 wavefronts x 4 rows) -> one partial row per chunk,
-    // in a fixed order
-    __shared__ float red[16][kNumSums];
+    // Sixteen sums held by sixteen lanes: a halving exchange inside each row of 16 lanes (after the
+    // level that pairs lanes differing in bit b, a lane keeps only the sums whose index has its own
+    // bit b) leaves lane l of a row with that row's total of sum l & 15, in 8+4+2+1 DPP additions.
+    // Then LDS (4 wavefronts x 4 rows) -> one partial row per chunk, in a fixed order.
+    static_assert(kNumSums == 16, "the exchange below is written for 16 sums");
+    {
+        const bool b3 = lane & 8u, b2 = lane & 4u, b1 = lane & 2u, b0 = lane & 1u;
 #pragma unroll
-    for (int i = 0; i < (int)kNumSums; ++i) {
-        const float s = row_sum(acc[i]);
-        if ((lane & 15u) == 0) red[wave * 4 + (lane >> 4)][i] = s;
+        for (int i = 0; i < 8; ++i) {                     // partner lane ^ 8 (row_ror:8)
+            const float keep = b3 ? acc[i + 8] : acc[i], send = b3 ? acc[i] : acc[i + 8];
+            acc[i] = keep + dpp<0x128, 0xf>(0.f, send);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                     // partner 7 - (lane & 7) in the same half (row_half_mirror)
+            const float keep = b2 ? acc[i + 4] : acc[i], send = b2 ? acc[i] : acc[i + 4];
+            acc[i] = keep + dpp<0x141, 0xf>(0.f, send);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {                     // partner lane ^ 2
+            const float keep = b1 ? acc[i + 2] : acc[i], send = b1 ? acc[i] : acc[i + 2];
+            acc[i] = keep + dpp<0x4E, 0xf>(0.f, send);
+        }
+        const float keep = b0 ? acc[1] : acc[0], send = b0 ? acc[0] : acc[1];
+        acc[0] = keep + dpp<0xB1, 0xf>(0.f, send);       // partner lane ^ 1
     }
+    __shared__ float red[16 * kNumSums];                  // [wavefront * 4 + row][sum]
+    red[threadIdx.x] = acc[0];
     __syncthreads();
     if (threadIdx.x < kNumSums) {
         float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) s += red[q][threadIdx.x];
+        for (int q = 0; q < 16; ++q) s += red[q * kNumSums + threadIdx.x];
         partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] = s;
     }
 }
