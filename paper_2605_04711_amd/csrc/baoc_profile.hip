@@ -501,15 +501,18 @@ __device__ __forceinline__ Prefixes distinct_prefixes(const uint32_t* __restrict
     return d;
 }
 
-// h[u * nb + bin] += 1 for the distinct prefixes that equal hi; slots 2 and 3 are rarely in use
+// h[u * nb + bin] += 1 for the slot u whose prefix equals hi (the prefixes are distinct, so at most
+// one does): the slot is selected first and a single LDS atomic follows.  Slots 2 and 3 are rarely in use.
 __device__ __forceinline__ void count_match(uint32_t* h, const Prefixes& d, uint32_t nb, uint32_t hi, uint32_t bin)
 {
-    if (hi == d.pre[0]) atomicAdd(&h[bin], 1u);
-    if (hi == d.pre[1]) atomicAdd(&h[nb + bin], 1u);
+    bool hit = hi == d.pre[0];
+    uint32_t at = bin;
+    if (hi == d.pre[1]) { at = nb + bin; hit = true; }
     if (d.n > 2) {
-        if (hi == d.pre[2]) atomicAdd(&h[2 * nb + bin], 1u);
-        if (hi == d.pre[3]) atomicAdd(&h[3 * nb + bin], 1u);
+        if (hi == d.pre[2]) { at = 2 * nb + bin; hit = true; }
+        if (hi == d.pre[3]) { at = 3 * nb + bin; hit = true; }
     }
+    if (hit) atomicAdd(&h[at], 1u);
 }
 
 constexpr uint32_t kHistGrid = 2048;     // persistent workgroups of the histogram passes (8 per CU)
