@@ -154,9 +154,11 @@ class Profiler:
     """baoc_profile_begin / step / finalize / end around a torch-owned workspace.
 
     blocks: sequence of (offset, numel[, rows, cols]) or objects with those attributes.
+    workspace: optional caller-owned uint8 device tensor of at least workspace_bytes(blocks, params)
+    bytes, 256-byte aligned; its previous contents do not matter.
     """
 
-    def __init__(self, blocks, params=None, device="cuda:0", **kw):
+    def __init__(self, blocks, params=None, device="cuda:0", workspace=None, **kw):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -167,11 +169,15 @@ class Profiler:
         _check(self.lib.baoc_profile_workspace_bytes(self._blocks, self.n_blocks, C.byref(self.params), C.byref(nbytes)),
                "baoc_profile_workspace_bytes")
         self.device = torch.device(device)
-        self.workspace = torch.empty(nbytes.value, dtype=torch.uint8, device=self.device)
+        if workspace is None:
+            workspace = torch.empty(nbytes.value, dtype=torch.uint8, device=self.device)
+        elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != self.device:
+            raise TypeError(f"workspace must be a contiguous uint8 tensor on {self.device}")
+        self.workspace = workspace
         self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(self.lib.baoc_profile_begin(self._blocks, self.n_blocks, C.byref(self.params),
-                                               self.workspace.data_ptr(), nbytes.value, C.byref(self._h)),
+                                               self.workspace.data_ptr(), self.workspace.numel(), C.byref(self._h)),
                    "baoc_profile_begin")
 
     def step(self, grad, stream=None):

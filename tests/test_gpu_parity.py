@@ -130,6 +130,38 @@ def test_full_candidate_space_with_soft_preference(env):
     assert_risk_close(risk, orisk, "k21")
 
 
+def test_dirty_workspace_and_windows_back_to_back(env):
+    """begin must not depend on what the workspace held: it is filled with 0xFF bytes (NaN patterns) first,
+    then reused for a second window after end; finalize in the middle of a window leaves the window intact."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload("bf16", 3)
+    params = binding.default_profile_params(grad_dtype=1)
+    ws = torch.full((binding.workspace_bytes(w.blocks, params) + 4096,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    shapes = [(b.rows, b.cols) for b in w.blocks]
+    buf = device.new_buffer(w)
+    for window, (seed, T) in enumerate([(11, 5), (12, 3)]):
+        prof = binding.Profiler(w.blocks, params, workspace=ws)
+        orc = OracleRunner(w.blocks, None, **oracle_params(params))
+        for t in range(1, T + 1):
+            device.fill(w, buf, seed, t)
+            prof.step(buf)
+            orc.step_from_device(buf)
+            if t == 2:                                       # a look at the statistics in mid-window
+                stats, _ = prof.finalize()
+                ostats, _ = orc.finalize(w.configs, shapes=shapes)
+                for i in range(len(w.blocks)):
+                    assert_stats_close(stats[i], ostats[i], f"window {window} mid block {i}")
+        stats, risk = prof.finalize(w.configs)
+        ostats, orisk = orc.finalize(w.configs, shapes=shapes)
+        for i in range(len(w.blocks)):
+            assert_stats_close(stats[i], ostats[i], f"window {window} block {i}")
+            assert_risk_close(risk[i], orisk[i], f"window {window} block {i}")
+            m, v, _ = prof.state(i)
+            assert np.array_equal(to_host_bits(m).view(np.uint32), orc.state[i].m.view(np.uint32))
+            assert np.array_equal(to_host_bits(v).view(np.uint32), orc.state[i].v.view(np.uint32))
+        prof.close()
+
+
 def test_two_runs_give_identical_bits(env):
     w = ragged_workload("f32", 1)
     a = run_both(env, w, 4, chunk_groups=2)[1]
