@@ -9,7 +9,14 @@ namespace baoc {
 
 constexpr uint32_t kQB = 256;            // coordinates per 8-bit absmax group = one wavefront x 4
 constexpr uint32_t kNumSums = 16;        // floats in one partial-sum row
-constexpr uint32_t kDefaultChunkGroups = 4;    // one group per wavefront: no wavefront waits on its own stores
+
+// Launch shape of the step kernel, per gradient type (fp32, bf16): adjacent groups a wavefront
+// loads together and workgroups resident per compute unit.  Measured: a DRAM stream of 4 reads and
+// 3 writes per coordinate runs fastest with few, fat requesters; more resident wavefronts only add
+// row conflicts.  A chunk is one round of a workgroup (4 wavefronts x groups_per_wave groups).
+constexpr uint32_t kDefaultGroupsPerWave[2] = {1, 2};
+constexpr uint32_t kDefaultResidentWorkgroups[2] = {4, 3};
+constexpr uint32_t kLdsBytesPerCU = 160 * 1024;   // gfx950
 
 // order of the sums in a partial row and in the per-block raw record
 enum Sum : int {

@@ -182,7 +182,11 @@ template <> struct GradIO<BAOC_GRAD_BF16> {
 // ---------------------------------------------------------------------------
 
 // FIRST: the states are known to be zero (first step after begin), so they are not read.
-template <int GT, bool FIRST>
+// G: quantisation groups a wavefront takes per round, next to each other (G * 1 KB of m and of v per
+// wavefront and round); a workgroup covers 4 * G groups per round.  The loads of a round are issued
+// together, one round ahead of their use.  With the default chunking a chunk is a single round, so no
+// wavefront ever waits on its own stores.
+template <int GT, bool FIRST, int G>
 __global__ __launch_bounds__(256) void k_step(
     const typename GradIO<GT>::elem* __restrict__ grad,
     float* __restrict__ m_all, float* __restrict__ v_all,
@@ -200,43 +204,53 @@ __global__ __launch_bounds__(256) void k_step(
 #pragma unroll
     for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.f;
 
-    // The loads of a group are issued one iteration ahead of their use, so a wavefront always has
-    // the next 22/28 bytes per coordinate in flight while it works on the current ones.
     typedef typename IO::vec4 GV;
-    f4 nm = {0.f, 0.f, 0.f, 0.f}, nv = {0.f, 0.f, 0.f, 0.f};
-    GV np = {}, ng = {};
-    auto issue = [&](uint32_t grp) {
-        const uint32_t e = grp * kQB + lane * 4;
-        const uint64_t si = ck.state_start + e;           // states are padded to whole groups
-        if (!FIRST) { nm = ld_stream<f4>(m_all + si); nv = ld_stream<f4>(v_all + si); np = IO::loadv(gp_all + si); }
-        if (vec_ok && e + 4 <= ck.count) ng = IO::loadv(gsrc + e);
+    f4 nm[G], nv[G];
+    GV np[G], ng[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) { nm[i] = f4{0.f, 0.f, 0.f, 0.f}; nv[i] = nm[i]; np[i] = GV{}; ng[i] = GV{}; }
+    auto issue = [&](uint32_t first) {                    // first: the wavefront's first group of a round
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const uint32_t grp = first + i;
+            if (grp < ngroups) {
+                const uint32_t e = grp * kQB + lane * 4;
+                const uint64_t si = ck.state_start + e;   // states are padded to whole groups
+                if (!FIRST) { nm[i] = ld_stream<f4>(m_all + si); nv[i] = ld_stream<f4>(v_all + si); np[i] = IO::loadv(gp_all + si); }
+                if (vec_ok && e + 4 <= ck.count) ng[i] = IO::loadv(gsrc + e);
+            }
+        }
     };
-    if (wave < ngroups) issue(wave);
+    if (wave * G < ngroups) issue(wave * G);
 
-    for (uint32_t grp = wave; grp < ngroups; grp += 4) {
+    for (uint32_t first = wave * G; first < ngroups; first += 4 * G) {
+      f4 cm[G], cv[G];
+      GV cp[G], cg[G];
+#pragma unroll
+      for (int i = 0; i < G; ++i) { cm[i] = nm[i]; cv[i] = nv[i]; cp[i] = np[i]; cg[i] = ng[i]; }
+      if (first + 4 * G < ngroups) issue(first + 4 * G);
+#pragma unroll
+      for (int i = 0; i < G; ++i) {
+        const uint32_t grp = first + i;
+        if (grp >= ngroups) break;
         const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
         const uint64_t si = ck.state_start + e;
         float* m_dst = m_all + si;                        // store addresses formed early: the stores then
         float* v_dst = v_all + si;                        // leave as soon as the updated states exist
         float g[4], p[4], m[4], v[4];
-        {
-            const f4 cm = nm, cv = nv;
-            const GV cp = np, cg = ng;
-            if (grp + 4 < ngroups) issue(grp + 4);
-            if (FIRST) {
+        if (FIRST) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
-            } else {
-                m[0] = cm.x; m[1] = cm.y; m[2] = cm.z; m[3] = cm.w;
-                v[0] = cv.x; v[1] = cv.y; v[2] = cv.z; v[3] = cv.w;
-                IO::unpack(cp, p);
-            }
-            if (vec_ok && e + 4 <= ck.count) {
-                IO::unpack(cg, g);
-            } else {                                      // ragged tail or unaligned block start
+            for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
+        } else {
+            m[0] = cm[i].x; m[1] = cm[i].y; m[2] = cm[i].z; m[3] = cm[i].w;
+            v[0] = cv[i].x; v[1] = cv[i].y; v[2] = cv[i].z; v[3] = cv[i].w;
+            IO::unpack(cp[i], p);
+        }
+        if (vec_ok && e + 4 <= ck.count) {
+            IO::unpack(cg[i], g);
+        } else {                                          // ragged tail or unaligned block start
 #pragma unroll
-                for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
-            }
+            for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
         }
 
         // Eq. 3 in fp32: the new term is rounded, then one fused multiply-add
@@ -298,6 +312,7 @@ __global__ __launch_bounds__(256) void k_step(
                 acc[EV_8] = __builtin_fmaf(dv, dv, acc[EV_8]);
             }
         }
+      }
     }
 
     // Sixteen sums held by sixteen lanes: a halving exchange inside each row of 16 lanes (after the
@@ -1056,7 +1071,8 @@ static int check_params(const baoc_profile_params* p)
     if (!(p->eps >= 0.0) || !(p->eps_update >= 0.f)) return BAOC_ERR_INVALID;
     if (p->grad_dtype != BAOC_GRAD_F32 && p->grad_dtype != BAOC_GRAD_BF16) return BAOC_ERR_INVALID;
     if (p->quant_block != kQB) return BAOC_ERR_UNSUPPORTED;
-    if (p->chunk_groups > 4096) return BAOC_ERR_INVALID;
+    if (p->chunk_groups > 4096 || p->groups_per_wave > 2) return BAOC_ERR_INVALID;
+    if (p->resident_workgroups != 0 && (p->resident_workgroups < 3 || p->resident_workgroups > 8)) return BAOC_ERR_INVALID;
     return BAOC_OK;
 }
 
@@ -1082,7 +1098,8 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         if (iv[i - 1].first + iv[i - 1].second > iv[i].first) return BAOC_ERR_INVALID;
     if (max_end) *max_end = end_max;
 
-    const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : kDefaultChunkGroups;
+    const uint32_t gpw = prm->groups_per_wave ? prm->groups_per_wave : kDefaultGroupsPerWave[prm->grad_dtype];
+    const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : 4 * gpw;
     Plan& P = *out;
     P.n_chunks = 0; P.rows.resize(n); P.slabs.clear();
     uint64_t state = 0;
@@ -1169,7 +1186,8 @@ extern "C" void baoc_profile_params_default(baoc_profile_params* p)
 {
     if (!p) return;
     p->beta_m = 0.9f; p->beta_v = 0.999f; p->beta_rho = 0.9; p->eps = 1e-12; p->eps_update = 1e-8f;
-    p->quant_block = kQB; p->grad_dtype = BAOC_GRAD_F32; p->chunk_groups = 0;
+    p->quant_block = kQB; p->grad_dtype = BAOC_GRAD_F32;
+    p->chunk_groups = 0; p->groups_per_wave = 0; p->resident_workgroups = 0;
 }
 
 extern "C" int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
@@ -1234,16 +1252,26 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
     const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
     float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
     const uint32_t grid = (uint32_t)P.n_chunks;
-    typedef float* fp; typedef uint16_t* hp;
     const bool first = h->steps == 0;
+    const uint32_t gpw = q.groups_per_wave ? q.groups_per_wave : kDefaultGroupsPerWave[q.grad_dtype];
+    // The first launch is bound by its arithmetic and runs at full residency.  Later launches are bound
+    // by DRAM and run with fewer resident workgroups: each is given so much unused LDS that only
+    // `resident` of them fit a compute unit (allocations are counted in multiples of 2 KB here).
+    const uint32_t resident = q.resident_workgroups ? q.resident_workgroups : kDefaultResidentWorkgroups[q.grad_dtype];
+    uint32_t lds = 0;
+    if (!first && resident < 8) lds = kLdsBytesPerCU / resident / 2048 * 2048 - kNumSums * 16 * 4;
     if (q.grad_dtype == BAOC_GRAD_F32) {
-        auto kern = first ? k_step<BAOC_GRAD_F32, true> : k_step<BAOC_GRAD_F32, false>;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st,
-                           static_cast<const float*>(d_grad_flat), m, v, reinterpret_cast<fp>(h->ws + P.off_gp), ch, part, k);
+        float* gp = reinterpret_cast<float*>(h->ws + P.off_gp);
+        const float* g = static_cast<const float*>(d_grad_flat);
+        auto kern = gpw == 2 ? (first ? k_step<BAOC_GRAD_F32, true, 2> : k_step<BAOC_GRAD_F32, false, 2>)
+                             : (first ? k_step<BAOC_GRAD_F32, true, 1> : k_step<BAOC_GRAD_F32, false, 1>);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g, m, v, gp, ch, part, k);
     } else {
-        auto kern = first ? k_step<BAOC_GRAD_BF16, true> : k_step<BAOC_GRAD_BF16, false>;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st,
-                           static_cast<const uint16_t*>(d_grad_flat), m, v, reinterpret_cast<hp>(h->ws + P.off_gp), ch, part, k);
+        uint16_t* gp = reinterpret_cast<uint16_t*>(h->ws + P.off_gp);
+        const uint16_t* g = static_cast<const uint16_t*>(d_grad_flat);
+        auto kern = gpw == 2 ? (first ? k_step<BAOC_GRAD_BF16, true, 2> : k_step<BAOC_GRAD_BF16, false, 2>)
+                             : (first ? k_step<BAOC_GRAD_BF16, true, 1> : k_step<BAOC_GRAD_BF16, false, 1>);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g, m, v, gp, ch, part, k);
     }
     h->steps += 1;
     double* slab_sums = reinterpret_cast<double*>(h->ws + P.off_slabsums);

@@ -21,9 +21,9 @@ def env():
     return dict(torch=torch, B=B, binding=binding, device=device)
 
 
-def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED, theta_dtype=None):
+def run_both(env, w, T, only=None, chunk_groups=0, check_state=True, seed=SEED, theta_dtype=None, **shape):
     torch, binding, device = env["torch"], env["binding"], env["device"]
-    params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=chunk_groups)
+    params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=chunk_groups, **shape)
     prof = binding.Profiler(w.blocks, params)
     orc = OracleRunner(w.blocks, only, **oracle_params(params))
     buf = device.new_buffer(w)
@@ -93,6 +93,15 @@ def test_ragged_blocks_unaligned_offsets_gaps_and_order(env, dtype, pad, chunk_g
     torch = env["torch"]
     run_both(env, ragged_workload(dtype, pad, reverse), 5, chunk_groups=chunk_groups,
              theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("groups_per_wave,chunk_groups,resident", [(1, 0, 8), (2, 0, 3), (2, 3, 5), (1, 9, 0), (2, 20, 0), (2, 1, 4)])
+def test_launch_shapes_leave_the_results_alone(env, dtype, groups_per_wave, chunk_groups, resident):
+    """Chunks of one round and of several, whole and partial rounds, one or two groups per wavefront,
+    limited and unlimited residency: the same statistics and bit-identical states."""
+    run_both(env, ragged_workload(dtype, 1), 4, chunk_groups=chunk_groups, groups_per_wave=groups_per_wave,
+             resident_workgroups=resident, theta_dtype=env["torch"].float32)
 
 
 def test_resnet50_all_blocks_all_steps(env):

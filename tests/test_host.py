@@ -65,6 +65,10 @@ def test_layout_validation():
     assert status([(0, 10)], quant_block=128) == binding.ERR_UNSUPPORTED
     assert status([(0, 10)], beta_m=1.0) == binding.ERR_INVALID
     assert status([(0, 10)], grad_dtype=7) == binding.ERR_INVALID
+    assert status([(0, 10)], groups_per_wave=3) == binding.ERR_INVALID
+    assert status([(0, 10)], resident_workgroups=2) == binding.ERR_INVALID
+    assert status([(0, 10)], resident_workgroups=9) == binding.ERR_INVALID
+    assert status([(0, 10)], chunk_groups=5000) == binding.ERR_INVALID
     assert status([(0, 1 << 33)]) == binding.ERR_UNSUPPORTED
     assert status([]) == binding.ERR_INVALID
     assert ws([(20, 10), (0, 20), (100, 7, 7, 1)]) > 0                     # any order, gaps, touching
