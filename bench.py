@@ -68,7 +68,7 @@ def cpu_baseline(w, ring, seed, params):
             pick.append(i); tot += w.blocks[i].numel
     if not pick:
         pick = [min(range(len(w.blocks)), key=lambda i: w.blocks[i].numel)]; tot = w.blocks[pick[0]].numel
-    steps = 2
+    steps = 6                                             # about 10 s on 16 cores
     data = [[to_host_bits(ring[t % len(ring)][w.blocks[i].offset:w.blocks[i].offset + w.blocks[i].numel]) for i in pick]
             for t in range(steps)]
     blocks = [oracle.Block(w.blocks[i].numel, **oracle_params(params)) for i in pick]
