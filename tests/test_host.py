@@ -217,3 +217,23 @@ def test_allocate_full_size_instances_properties(name):
               options=dict(mip_rel_gap=0.0, time_limit=60))
     if ip.success and ip.status == 0:
         assert obj <= ip.fun + 1e-6 and obj >= ip.fun - 1e-5 * max(1.0, abs(ip.fun))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_traffic_file_is_read_per_workload():
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec); spec.loader.exec_module(bench)
+    path = os.path.join(root, "profiles", "k_step_pmc_traffic.txt")
+    t = bench.read_traffic(path, "llama7b")
+    assert t is not None and 1.0 <= t / (22 * 6738415616) < 1.02          # measured traffic close to the algorithmic bytes
+    assert bench.read_traffic(path, "resnet50") is None and bench.read_traffic(path + ".missing", "llama7b") is None
