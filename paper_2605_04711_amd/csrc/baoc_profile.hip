@@ -224,95 +224,95 @@ __global__ __launch_bounds__(256) void k_step(
     if (wave * G < ngroups) issue(wave * G);
 
     for (uint32_t first = wave * G; first < ngroups; first += 4 * G) {
-      f4 cm[G], cv[G];
-      GV cp[G], cg[G];
+        f4 cm[G], cv[G];
+        GV cp[G], cg[G];
 #pragma unroll
-      for (int i = 0; i < G; ++i) { cm[i] = nm[i]; cv[i] = nv[i]; cp[i] = np[i]; cg[i] = ng[i]; }
-      if (first + 4 * G < ngroups) issue(first + 4 * G);
+        for (int i = 0; i < G; ++i) { cm[i] = nm[i]; cv[i] = nv[i]; cp[i] = np[i]; cg[i] = ng[i]; }
+        if (first + 4 * G < ngroups) issue(first + 4 * G);
 #pragma unroll
-      for (int i = 0; i < G; ++i) {
-        const uint32_t grp = first + i;
-        if (grp >= ngroups) break;
-        const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
-        const uint64_t si = ck.state_start + e;
-        float* m_dst = m_all + si;                        // store addresses formed early: the stores then
-        float* v_dst = v_all + si;                        // leave as soon as the updated states exist
-        float g[4], p[4], m[4], v[4];
-        if (FIRST) {
+        for (int i = 0; i < G; ++i) {
+            const uint32_t grp = first + i;
+            if (grp >= ngroups) break;
+            const uint32_t e = grp * kQB + lane * 4;          // first of this lane's 4 coordinates
+            const uint64_t si = ck.state_start + e;
+            float* m_dst = m_all + si;                        // store addresses formed early: the stores then
+            float* v_dst = v_all + si;                        // leave as soon as the updated states exist
+            float g[4], p[4], m[4], v[4];
+            if (FIRST) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
-        } else {
-            m[0] = cm[i].x; m[1] = cm[i].y; m[2] = cm[i].z; m[3] = cm[i].w;
-            v[0] = cv[i].x; v[1] = cv[i].y; v[2] = cv[i].z; v[3] = cv[i].w;
-            IO::unpack(cp[i], p);
-        }
-        if (vec_ok && e + 4 <= ck.count) {
-            IO::unpack(cg[i], g);
-        } else {                                          // ragged tail or unaligned block start
-#pragma unroll
-            for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
-        }
-
-        // Eq. 3 in fp32: the new term is rounded, then one fused multiply-add
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float tm = k.om_m * g[j];
-            const float tv = (k.om_v * g[j]) * g[j];
-            m[j] = __builtin_fmaf(k.beta_m, m[j], tm);
-            v[j] = __builtin_fmaf(k.beta_v, v[j], tv);
-        }
-        {
-            f4 t = {m[0], m[1], m[2], m[3]};
-            st_stream<f4>(m_dst, t);
-            f4 s = {v[0], v[1], v[2], v[3]};
-            st_stream<f4>(v_dst, s);
-        }
-        IO::store4(gp_all + si, g);
-
-        // group absmax of the 256 coordinates this wavefront holds
-        const float a_m = wave_max_nonneg(fmaxf(fmaxf(fabsf(m[0]), fabsf(m[1])), fmaxf(fabsf(m[2]), fabsf(m[3]))));
-        const float a_v = wave_max_nonneg(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
-        // 8-bit code = rint(x * (L / a)) decided in fp32 with a correctly rounded quotient;
-        // an infinite scale (a == 0 or tiny) means all codes are 0
-        float s_m = 127.0f / a_m, s_v = 255.0f / a_v;
-        s_m = s_m < INFINITY ? s_m : 0.f;
-        s_v = s_v < INFINITY ? s_v : 0.f;
-        const float d_m = a_m * (1.0f / 127.0f), d_v = a_v * (1.0f / 255.0f);
-
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float mj = m[j], vj = v[j];
-            acc[S_GG] = __builtin_fmaf(g[j], g[j], acc[S_GG]);
-            acc[S_GP] = __builtin_fmaf(g[j], p[j], acc[S_GP]);
-            acc[S_MM] = __builtin_fmaf(mj, mj, acc[S_MM]);
-            acc[S_V1] += vj;
-            acc[S_VV] = __builtin_fmaf(vj, vj, acc[S_VV]);
-            const float u32 = direction(mj, vj, k.eps_u);
-            acc[U0] = __builtin_fmaf(u32, u32, acc[U0]);
-            {   // bf16 round trip
-                float mb, vb;
-                bf16_round2(mj, vj, mb, vb);
-                const float ub = direction(mb, vb, k.eps_u);
-                const float du = ub - u32, dm = mb - mj, dv = vb - vj;
-                acc[U1_16] = __builtin_fmaf(u32, ub, acc[U1_16]);
-                acc[D_16] = __builtin_fmaf(du, du, acc[D_16]);
-                acc[U2_16] = __builtin_fmaf(ub, ub, acc[U2_16]);
-                acc[EM_16] = __builtin_fmaf(dm, dm, acc[EM_16]);
-                acc[EV_16] = __builtin_fmaf(dv, dv, acc[EV_16]);
+                for (int j = 0; j < 4; ++j) m[j] = v[j] = p[j] = 0.f;
+            } else {
+                m[0] = cm[i].x; m[1] = cm[i].y; m[2] = cm[i].z; m[3] = cm[i].w;
+                v[0] = cv[i].x; v[1] = cv[i].y; v[2] = cv[i].z; v[3] = cv[i].w;
+                IO::unpack(cp[i], p);
             }
-            {   // block-wise absmax 8-bit round trip
-                const float mb = __builtin_rintf(mj * s_m) * d_m;
-                const float vb = __builtin_rintf(vj * s_v) * d_v;
-                const float ub = direction(mb, vb, k.eps_u);
-                const float du = ub - u32, dm = mb - mj, dv = vb - vj;
-                acc[U1_8] = __builtin_fmaf(u32, ub, acc[U1_8]);
-                acc[D_8] = __builtin_fmaf(du, du, acc[D_8]);
-                acc[U2_8] = __builtin_fmaf(ub, ub, acc[U2_8]);
-                acc[EM_8] = __builtin_fmaf(dm, dm, acc[EM_8]);
-                acc[EV_8] = __builtin_fmaf(dv, dv, acc[EV_8]);
+            if (vec_ok && e + 4 <= ck.count) {
+                IO::unpack(cg[i], g);
+            } else {                                          // ragged tail or unaligned block start
+#pragma unroll
+                for (int j = 0; j < 4; ++j) g[j] = (e + j < ck.count) ? IO::load1(gsrc + e + j) : 0.f;
+            }
+
+            // Eq. 3 in fp32: the new term is rounded, then one fused multiply-add
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float tm = k.om_m * g[j];
+                const float tv = (k.om_v * g[j]) * g[j];
+                m[j] = __builtin_fmaf(k.beta_m, m[j], tm);
+                v[j] = __builtin_fmaf(k.beta_v, v[j], tv);
+            }
+            {
+                f4 t = {m[0], m[1], m[2], m[3]};
+                st_stream<f4>(m_dst, t);
+                f4 s = {v[0], v[1], v[2], v[3]};
+                st_stream<f4>(v_dst, s);
+            }
+            IO::store4(gp_all + si, g);
+
+            // group absmax of the 256 coordinates this wavefront holds
+            const float a_m = wave_max_nonneg(fmaxf(fmaxf(fabsf(m[0]), fabsf(m[1])), fmaxf(fabsf(m[2]), fabsf(m[3]))));
+            const float a_v = wave_max_nonneg(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+            // 8-bit code = rint(x * (L / a)) decided in fp32 with a correctly rounded quotient;
+            // an infinite scale (a == 0 or tiny) means all codes are 0
+            float s_m = 127.0f / a_m, s_v = 255.0f / a_v;
+            s_m = s_m < INFINITY ? s_m : 0.f;
+            s_v = s_v < INFINITY ? s_v : 0.f;
+            const float d_m = a_m * (1.0f / 127.0f), d_v = a_v * (1.0f / 255.0f);
+
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float mj = m[j], vj = v[j];
+                acc[S_GG] = __builtin_fmaf(g[j], g[j], acc[S_GG]);
+                acc[S_GP] = __builtin_fmaf(g[j], p[j], acc[S_GP]);
+                acc[S_MM] = __builtin_fmaf(mj, mj, acc[S_MM]);
+                acc[S_V1] += vj;
+                acc[S_VV] = __builtin_fmaf(vj, vj, acc[S_VV]);
+                const float u32 = direction(mj, vj, k.eps_u);
+                acc[U0] = __builtin_fmaf(u32, u32, acc[U0]);
+                {   // bf16 round trip
+                    float mb, vb;
+                    bf16_round2(mj, vj, mb, vb);
+                    const float ub = direction(mb, vb, k.eps_u);
+                    const float du = ub - u32, dm = mb - mj, dv = vb - vj;
+                    acc[U1_16] = __builtin_fmaf(u32, ub, acc[U1_16]);
+                    acc[D_16] = __builtin_fmaf(du, du, acc[D_16]);
+                    acc[U2_16] = __builtin_fmaf(ub, ub, acc[U2_16]);
+                    acc[EM_16] = __builtin_fmaf(dm, dm, acc[EM_16]);
+                    acc[EV_16] = __builtin_fmaf(dv, dv, acc[EV_16]);
+                }
+                {   // block-wise absmax 8-bit round trip
+                    const float mb = __builtin_rintf(mj * s_m) * d_m;
+                    const float vb = __builtin_rintf(vj * s_v) * d_v;
+                    const float ub = direction(mb, vb, k.eps_u);
+                    const float du = ub - u32, dm = mb - mj, dv = vb - vj;
+                    acc[U1_8] = __builtin_fmaf(u32, ub, acc[U1_8]);
+                    acc[D_8] = __builtin_fmaf(du, du, acc[D_8]);
+                    acc[U2_8] = __builtin_fmaf(ub, ub, acc[U2_8]);
+                    acc[EM_8] = __builtin_fmaf(dm, dm, acc[EM_8]);
+                    acc[EV_8] = __builtin_fmaf(dv, dv, acc[EV_8]);
+                }
             }
         }
-      }
     }
 
     // Sixteen sums held by sixteen lanes: a halving exchange inside each row of 16 lanes (after the
