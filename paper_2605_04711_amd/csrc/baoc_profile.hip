@@ -751,17 +751,21 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
         bool ok[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) ok[k] = tile_col(t.vec, lane, k) < t.ncols;
-        float cs[4] = {0.f, 0.f, 0.f, 0.f}, psum = 0.f;
+        // Column sums and the sum of p run over up to 256 rows per lane: kept in fp64 so that a constant
+        // v (rank one, p constant) comes out as such to ~1e-7 instead of the ~1e-5 of a long fp32 chain.
+        double cs[4] = {0.0, 0.0, 0.0, 0.0}, psum = 0.0;
         float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
         auto consume = [&](const float x[4]) {
+            float prow = 0.f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                cs[k] += x[k];
+                cs[k] += (double)x[k];
                 if (ok[k]) {
                     atomicAdd(&h[(__builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu) >> 20], 1u);
-                    if (want_p) psum += __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                    if (want_p) prow += __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
                 }
             }
+            psum += (double)prow;
             return wave_sum((x[0] + x[1]) + (x[2] + x[3]));
         };
         uint32_t r = t.row0;
@@ -786,9 +790,9 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
         float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (ok[k]) cp[tile_col(t.vec, lane, k)] = cs[k];
-        psum = wave_sum(psum);
-        if (lane == 0) psumpart[t.task] = psum;
+            if (ok[k]) cp[tile_col(t.vec, lane, k)] = (float)cs[k];
+        const float ptile = wave_sum((float)psum);
+        if (lane == 0) psumpart[t.task] = ptile;
     }
     __syncthreads();
     uint32_t* out = hist_all + (uint64_t)m.block * 4 * kBins;
@@ -851,7 +855,7 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
     __syncthreads();
     if (t.valid) {
         const double mu = mu_all[t.mat];
-        const float inv_mu = mu != 0.0 ? (float)(1.0 / mu) : 0.f;        // S~ = 0 when mu = 0
+        // c_j / mu is formed in fp64 (mu may lie below the fp32 normal range); S~ = 0 when mu = 0
         float inv_pbar = 0.f;
         if (want_C) inv_pbar = (float)((double)((uint64_t)m.rows * m.cols) / rec_all[(uint64_t)m.block * kRecDoubles + R_PSUM]);
         bool ok[4]; float cm[4];
@@ -859,7 +863,7 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
         for (int k = 0; k < 4; ++k) {
             const uint32_t c = tile_col(t.vec, lane, k);
             ok[k] = c < t.ncols;
-            cm[k] = ok[k] ? cvec[m.off_c + t.col0 + c] * inv_mu : 0.f;
+            cm[k] = (ok[k] && mu != 0.0) ? (float)((double)cvec[m.off_c + t.col0 + c] / mu) : 0.f;
         }
         const uint64_t first = (uint64_t)t.row0 * m.cols + t.col0;
         const float* row = v_all + m.state_start + first;

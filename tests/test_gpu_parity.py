@@ -192,6 +192,41 @@ def test_constant_gradient_direction_is_one_and_snr_closed_form(env):
     assert st.n_cos == 15 and st.steps == 16
 
 
+@pytest.mark.parametrize("value", [0.37, 3.1e-5, 1e-21])
+def test_uniform_gradient_is_isotropic_rank_one_and_undistorted(env, value):
+    """Every coordinate sees the same gradient: v is constant, so A = 0 exactly and F (rank-one S) and C
+    (constant preconditioner) vanish up to the absolute tolerance; 1e-21 puts v below the fp32 normal range."""
+    torch, binding = env["torch"], env["binding"]
+    blocks = [(0, 300 * 260, 300, 260), (78_016, 5_000), (83_072, 1030 * 3, 1030, 3), (86_208, 513 * 1027, 513, 1027)]
+    n = 86_208 + 513 * 1027
+    params = binding.default_profile_params()
+    prof = binding.Profiler(blocks, params)
+    orc = OracleRunner([W.BlockSpec(f"u{i}", b[1], *(b[2:] if len(b) > 2 else (0, 0)), offset=b[0]) for i, b in enumerate(blocks)],
+                       None, **oracle_params(params))
+    g = torch.full((n,), value, device="cuda:0")
+    for _ in range(3):
+        prof.step(g)
+        orc.step_from_device(g)
+    theta = 0.02 * torch.randn(n, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(3))
+    stats, _ = prof.finalize(theta=theta)
+    ostats, _ = orc.finalize([(1, 1, 0, 0, 32)], shapes=[(b[2], b[3]) if len(b) > 2 else (0, 0) for b in blocks], theta=theta)
+    for i in range(len(blocks)):
+        assert stats[i].A == 0.0 and stats[i].q10 == stats[i].q90
+        assert abs(stats[i].F) <= 1e-6 and abs(stats[i].C) <= 1e-6, (i, stats[i].F, stats[i].C)
+        assert_stats_close(stats[i], ostats[i], f"uniform {value} block {i}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("scale", [1e-22, 1e-19, 1e-12, 1e8])
+def test_gradient_magnitudes_from_underflow_of_v_to_1e8(env, dtype, scale):
+    """v-hat identically zero (1e-22), sub-normal (1e-19), tiny and huge: same statistics as the oracle."""
+    w = ragged_workload(dtype, 1)
+    for b in w.blocks:
+        b.delta *= scale
+        b.sigma *= scale
+    run_both(env, w, 4, seed=77, theta_dtype=env["torch"].float32)
+
+
 def test_other_blocks_do_not_matter(env):
     torch, binding = env["torch"], env["binding"]
     blocks = [(0, 5000), (5003, 777), (6000, 30000)]
