@@ -58,7 +58,7 @@ typedef struct {
     float    beta_v;       /* EMA rate of the second moment, Eq. 3            (0.999) */
     double   beta_rho;     /* smoothing of the direction stability, Eq. 5     (0.9)   */
     double   eps;          /* epsilon of Sec. 3.3 / App. A.1                  (1e-12) */
-    float    eps_update;   /* epsilon inside u = m / (sqrt(v) + eps_update), Eq. 8 (1e-8) */
+    float    eps_update;   /* epsilon inside u = m / (sqrt(v) + eps_update), Eq. 8 (1e-8); > 0 */
     uint32_t quant_block;  /* coordinates per 8-bit absmax group; only 256 is built     */
     uint32_t grad_dtype;   /* BAOC_GRAD_F32 | BAOC_GRAD_BF16 (states are always fp32)   */
     /* Launch shape of the per-step kernel; 0 = the default measured best for the gradient type.

@@ -1072,7 +1072,7 @@ static int check_params(const baoc_profile_params* p)
     if (!p) return BAOC_ERR_INVALID;
     if (!(p->beta_m > 0.f && p->beta_m < 1.f) || !(p->beta_v > 0.f && p->beta_v < 1.f)) return BAOC_ERR_INVALID;
     if (!(p->beta_rho >= 0.0 && p->beta_rho < 1.0)) return BAOC_ERR_INVALID;
-    if (!(p->eps >= 0.0) || !(p->eps_update >= 0.f)) return BAOC_ERR_INVALID;
+    if (!(p->eps >= 0.0) || !(p->eps_update > 0.f)) return BAOC_ERR_INVALID;   // u = m / (sqrt(v) + eps_update) must exist where v = 0
     if (p->grad_dtype != BAOC_GRAD_F32 && p->grad_dtype != BAOC_GRAD_BF16) return BAOC_ERR_INVALID;
     if (p->quant_block != kQB) return BAOC_ERR_UNSUPPORTED;
     if (p->chunk_groups > 4096 || p->groups_per_wave > 2) return BAOC_ERR_INVALID;

@@ -227,6 +227,35 @@ def test_gradient_magnitudes_from_underflow_of_v_to_1e8(env, dtype, scale):
     run_both(env, w, 4, seed=77, theta_dtype=env["torch"].float32)
 
 
+def test_three_thousand_small_blocks(env):
+    """Blocks of 1..699 coordinates, some 7 x k and k x 2 matrices, tightly packed: one chunk and one
+    histogram set per block."""
+    rng = np.random.default_rng(5)
+    blocks = []
+    for i, n in enumerate(int(x) for x in rng.integers(1, 700, 3000)):
+        r, c = (7, n // 7) if (n % 7 == 0 and n >= 14) else (0, 0)
+        if n % 2 == 0 and i % 5 == 0:
+            r, c = n // 2, 2
+        blocks.append(W.BlockSpec(f"s{i}", n, r, c))
+    w = W.Workload("many", blocks, 3, "bf16", "cycle", **W.K6)
+    W.layout(w, 1); W.draw_stream_params(w, 9)
+    run_both(env, w, 3, seed=5, theta_dtype=env["torch"].bfloat16)
+
+
+def test_extreme_matrix_shapes(env):
+    blocks = [W._mat("wide2", 2, 300001), W._mat("tall2", 300001, 2), W._mat("sq1k", 1000, 1000), W._mat("odd", 257, 255),
+              W._mat("r1", 1, 5000), W._mat("c1", 5000, 1)]
+    w = W.Workload("shapes", blocks, 3, "f32", "cycle", **W.K6)
+    W.layout(w, 3); W.draw_stream_params(w, 4)
+    run_both(env, w, 3, seed=6, theta_dtype=env["torch"].float32)
+
+
+@pytest.mark.parametrize("kw", [dict(beta_m=0.5, beta_v=0.9, beta_rho=0.0), dict(eps=0.0), dict(eps=1e-3, eps_update=1e-2),
+                                dict(beta_m=0.999, beta_v=0.99999)])
+def test_profile_parameters_away_from_the_defaults(env, kw):
+    run_both(env, ragged_workload("f32", 1), 4, **kw)
+
+
 def test_other_blocks_do_not_matter(env):
     torch, binding = env["torch"], env["binding"]
     blocks = [(0, 5000), (5003, 777), (6000, 30000)]
