@@ -663,6 +663,9 @@ __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_a
 // ---------------------------------------------------------------------------
 
 constexpr uint32_t kTileRows = 256, kTileCols = 256;
+// Rows a wavefront loads before it consumes them.  Measured on the 7B layout (whole finalize): 1 row 22.7 ms,
+// 2 rows 19.9, 4 rows 20.5, 8 rows 23.0 -- as in the step kernel, more requests in flight are not better.
+constexpr uint32_t kRowsInFlight = 2;
 
 struct alignas(8) MatRow {
     uint64_t state_start;                 // first coordinate of the block in v
@@ -769,16 +772,16 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
             return wave_sum((x[0] + x[1]) + (x[2] + x[3]));
         };
         uint32_t r = t.row0;
-        for (; r + 4 <= t.row1; r += 4) {                       // four rows in flight
-            float x[4][4];
+        for (; r + kRowsInFlight <= t.row1; r += kRowsInFlight) {
+            float x[kRowsInFlight][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+            for (int q = 0; q < (int)kRowsInFlight; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < (int)kRowsInFlight; ++q) {
                 const float rs = consume(x[q]);
                 if (lane == 0) rp[(uint64_t)q * m.n_tiles] = rs;
             }
-            row += (uint64_t)4 * m.cols; rp += (uint64_t)4 * m.n_tiles;
+            row += (uint64_t)kRowsInFlight * m.cols; rp += (uint64_t)kRowsInFlight * m.n_tiles;
         }
         for (; r < t.row1; ++r) {
             float x[4];
@@ -892,17 +895,17 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
             }
         };
         uint32_t r = t.row0;
-        for (; r + 4 <= t.row1; r += 4) {
-            float x[4][4], th[4][4];
+        for (; r + kRowsInFlight <= t.row1; r += kRowsInFlight) {
+            float x[kRowsInFlight][4], th[kRowsInFlight][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < (int)kRowsInFlight; ++q) {
                 load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
                 if (want_C) load_tile_theta<TT>(trow + (uint64_t)q * m.cols, t.vec, talign, lane, t.ncols, th[q]);
                 else th[q][0] = th[q][1] = th[q][2] = th[q][3] = 0.f;
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) consume(x[q], th[q], rr[q]);
-            row += (uint64_t)4 * m.cols; trow += (uint64_t)4 * m.cols; rr += 4;
+            for (int q = 0; q < (int)kRowsInFlight; ++q) consume(x[q], th[q], rr[q]);
+            row += (uint64_t)kRowsInFlight * m.cols; trow += (uint64_t)kRowsInFlight * m.cols; rr += kRowsInFlight;
         }
         for (; r < t.row1; ++r) {
             float x[4], th[4] = {0.f, 0.f, 0.f, 0.f};
