@@ -79,9 +79,18 @@ def cpu_baseline(w, ring, seed, params):
             list(pool.map(lambda k: blocks[k].step(data[t][k]), range(len(pick))))
         list(pool.map(lambda b: b.finalize(), blocks))
     dt = time.perf_counter() - t0
+    # the same oracle on one core: the first sampled block alone, two steps + finalize
+    one = oracle.Block(w.blocks[pick[0]].numel, **oracle_params(params))
+    t1 = time.perf_counter()
+    for t in range(2):
+        one.step(data[t][0])
+    one.finalize()
+    dt1 = time.perf_counter() - t1
     return {"value": tot * steps / dt, "unit": "elements/s", "cores": cores, "kind": "oracle",
             "sample": f"{len(pick)} blocks ({tot:,} coordinates) of {w.name}, {steps} steps + finalize, threads over blocks",
-            "seconds": round(dt, 3)}
+            "seconds": round(dt, 3),
+            "one_core": {"value": w.blocks[pick[0]].numel * 2 / dt1, "unit": "elements/s",
+                         "sample": f"1 block ({w.blocks[pick[0]].numel:,} coordinates), 2 steps + finalize", "seconds": round(dt1, 3)}}
 
 
 def main():
