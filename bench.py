@@ -68,9 +68,9 @@ def cpu_baseline(w, ring, seed, params):
             pick.append(i); tot += w.blocks[i].numel
     if not pick:
         pick = [min(range(len(w.blocks)), key=lambda i: w.blocks[i].numel)]; tot = w.blocks[pick[0]].numel
-    steps = 6                                             # about 10 s on 16 cores
-    data = [[to_host_bits(ring[t % len(ring)][w.blocks[i].offset:w.blocks[i].offset + w.blocks[i].numel]) for i in pick]
-            for t in range(steps)]
+    steps = min(w.T, 16)                                  # up to a whole window of the sample: about 10 s on 16 cores
+    per_ring = [[to_host_bits(g[w.blocks[i].offset:w.blocks[i].offset + w.blocks[i].numel]) for i in pick] for g in ring]
+    data = [per_ring[t % len(ring)] for t in range(steps)]
     blocks = [oracle.Block(w.blocks[i].numel, **oracle_params(params)) for i in pick]
     cores = min(16, os.cpu_count() or 1, len(pick))
     t0 = time.perf_counter()
