@@ -33,5 +33,5 @@ def test_fullsize_sampled_blocks(env, name, T):  # noqa: F811
     print(f"{name}: oracle follows {len(only)} of {len(w.blocks)} blocks, "
           f"{sum(w.blocks[i].numel for i in only):,} of {w.numel:,} coordinates, T={T}", flush=True)
     torch = env["torch"]
-    run_both(env, w, T, only=only, check_state=False,
+    run_both(env, w, T, only=only, check_state=True,
              theta_dtype=torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32)
