@@ -237,4 +237,6 @@ def test_traffic_file_is_read_per_workload():
     path = os.path.join(root, "profiles", "k_step_pmc_traffic.txt")
     t = bench.read_traffic(path, "llama7b")
     assert t is not None and 1.0 <= t / (22 * 6738415616) < 1.02          # measured traffic close to the algorithmic bytes
+    u = bench.read_traffic(path, "unet")
+    assert u is not None and 1.0 <= u / (28 * 859520964) < 1.02
     assert bench.read_traffic(path, "resnet50") is None and bench.read_traffic(path + ".missing", "llama7b") is None
