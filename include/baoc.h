@@ -249,7 +249,8 @@ int baoc_allocate(const double* risk, const int64_t* mem_cost_bytes, const doubl
  * merged again.  out_block_of_unit (n_units) receives ascending block ids from 0; a
  * block's statistics are the parameter-weighted mean of its units.  All pointers HOST;
  * out_n_blocks and out_tau may be NULL.  Errors: INVALID (null, zero sizes, non-finite z,
- * negative weights, alpha outside [0,1]). */
+ * negative weights, alpha outside [0,1]), UNSUPPORTED (more than 32,768 units: tau is a
+ * quantile over all unit pairs, so time and memory grow with n_units^2). */
 int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
                    const double* weights, double alpha,
                    uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau);

@@ -103,6 +103,7 @@ extern "C" int baoc_partition(const uint64_t* unit_numel, const double* z, uint3
 {
     if (!unit_numel || !z || !out_block_of_unit || n_units == 0 || n_stats == 0) return BAOC_ERR_INVALID;
     if (!(alpha >= 0.0) || !(alpha <= 1.0)) return BAOC_ERR_INVALID;
+    if (n_units > 32768) return BAOC_ERR_UNSUPPORTED;             // tau looks at all unit pairs (8 bytes each)
     Ctx c{unit_numel, z, n_stats, std::vector<double>(n_stats, 1.0), 0.0};
     uint64_t total = 0;
     for (uint32_t j = 0; j < n_units; ++j) {
@@ -130,10 +131,13 @@ extern "C" int baoc_partition(const uint64_t* unit_numel, const double* z, uint3
     }
     double tau = 0.0;
     if (!pair.empty()) {
-        std::sort(pair.begin(), pair.end());
+        // the two order statistics that bracket position 0.75 (n - 1), by selection instead of a full sort
         const double pos = 0.75 * (double)(pair.size() - 1);
-        const size_t lo = (size_t)pos, hi = std::min(lo + 1, pair.size() - 1);
-        tau = pair[lo] + (pos - (double)lo) * (pair[hi] - pair[lo]);
+        const size_t lo = (size_t)pos;
+        std::nth_element(pair.begin(), pair.begin() + (std::ptrdiff_t)lo, pair.end());
+        const double at_lo = pair[lo];
+        const double at_hi = lo + 1 < pair.size() ? *std::min_element(pair.begin() + (std::ptrdiff_t)lo + 1, pair.end()) : at_lo;
+        tau = at_lo + (pos - (double)lo) * (at_hi - at_lo);
     }
 
     std::vector<Units> temp(n_units);

@@ -113,3 +113,6 @@ def test_library_rejects_bad_arguments():
         lib_partition([1, 0], np.zeros((2, 1)), None, 0.1)
     with pytest.raises(B.BaocError):
         lib_partition([1, 2], np.array([[0.0], [np.nan]]), None, 0.1)
+    with pytest.raises(B.BaocError) as e:                              # tau is a quantile over all unit pairs
+        lib_partition(np.ones(40000, np.uint64), np.zeros((40000, 1)), None, 0.0)
+    assert e.value.status == binding.ERR_UNSUPPORTED
