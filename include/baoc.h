@@ -145,7 +145,9 @@ int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
  * begin) and the per-block reduction.  Returns without waiting.  The gradient
  * buffer must stay valid until that stream work has run; afterwards the
  * caller may overwrite it (the library keeps its own copy of g_t as g_{t-1}).
- * Consecutive calls are consecutive samples.  Range: the sums of squares of a
+ * Consecutive calls are consecutive samples.  The step index is a launch argument kept
+ * on the host, so a captured HIP graph of this call must not be replayed as a later step.
+ * Range: the sums of squares of a
  * chunk are kept in fp32 before the fp64 stage, so gradient magnitudes up to about
  * 1e8 give finite statistics (beyond, sums of v^2 overflow and the error and noise
  * terms of that block come out inf or NaN); small magnitudes are safe down to the
