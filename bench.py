@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--sample-ratio", type=float, default=0.0,
+                    help="sparse coordinate sampling (Sec. 3.1): gather g[Omega] with this ratio before every step and profile "
+                         "the compact buffer; prints its own JSON line (not the headline metric)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "k_step_pmc_traffic.txt"))
     return ap.parse_args()
 
@@ -91,6 +94,52 @@ def cpu_baseline(w, ring, seed, params):
             "seconds": round(dt, 3),
             "one_core": {"value": w.blocks[pick[0]].numel * 2 / dt1, "unit": "elements/s",
                          "sample": f"1 block ({w.blocks[pick[0]].numel:,} coordinates), 2 steps + finalize", "seconds": round(dt1, 3)}}
+
+
+def sampled_windows(a, w, ring, theta, params, mem, tc, b_mem, cap):
+    """Window with the sparse-sampling front end: Omega drawn once, then per step one gather of g[Omega] into a
+    compact buffer and one profiler step on it; theta is gathered the same way for Eq. 6."""
+    import torch
+    import paper_2605_04711_amd as B
+    from paper_2605_04711_amd import binding
+    K, D, R = a.steps or w.T, w.numel, len(ring)
+    smp = binding.Sampler(w.blocks, a.sample_ratio, a.seed)
+    samples = sum(b[1] for b in smp.compact_blocks)
+    compact = torch.zeros(smp.compact_numel, dtype=ring[0].dtype, device=ring[0].device)
+    theta_c = smp.gather(theta)
+    esz = ring[0].element_size()
+
+    def window(steps):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prof = binding.Profiler(smp.compact_blocks, params, device=ring[0].device)
+        for t in range(steps):
+            ev[t][0].record(); smp.gather(ring[t % R], compact)
+            ev[t][1].record(); prof.step(compact)
+            ev[t][2].record()
+        stats, risk = prof.finalize(w.configs, theta=theta_c)
+        t2 = time.perf_counter()
+        B.allocate(risk, mem, tc, b_mem, cap)
+        t3 = time.perf_counter()
+        g_ms = [e[0].elapsed_time(e[1]) for e in ev]; s_ms = [e[1].elapsed_time(e[2]) for e in ev]
+        prof.close()
+        return t3 - t0, g_ms, s_ms, (t2 - t0) * 1e3 - sum(g_ms) - sum(s_ms)
+
+    if a.warmup > 0:
+        window(a.warmup)
+    total, g_ms, s_ms, rest_ms = window(K)
+    g_avg = sum(g_ms) / len(g_ms); s_avg = sum(s_ms[1:]) / max(1, len(s_ms) - 1)
+    gather_bytes = samples * (8 + 2 * esz)                # index, element read, element written
+    return {"metric": "gradient elements covered/sec with sparse sampling", "value": K * D / total, "unit": "elements/s",
+            "n_gpus": 1, "steps": K, "warmup": a.warmup, "ms_per_step": total * 1e3 / K, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"{w.name} with sampling ratio {a.sample_ratio}: {samples:,} of {D:,} coordinates in Omega, "
+                                   f"window of {K} x (gather + step) + finalize + allocate", "samples": samples},
+            "breakdown_ms": {"gather_avg": round(g_avg, 4), "step_avg": round(s_avg, 4), "begin_finalize": round(rest_ms, 3)},
+            "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": gather_bytes / (g_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": gather_bytes / (g_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": g_avg, "launches": len(g_ms)}}
 
 
 def main():
@@ -150,6 +199,9 @@ def main():
         return dict(total=t3 - t0, begin=t1 - t0, steps_and_finalize=t2 - t1, allocate=t3 - t2, step_ms=step_ms,
                     obj=obj, mem_used=m_used, choice=choice, stats=stats)
 
+    if a.sample_ratio > 0:
+        print(json.dumps(sampled_windows(a, w, ring, theta, params, mem, tc, b_mem, cap)))
+        return
     if a.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
