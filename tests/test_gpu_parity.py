@@ -256,6 +256,34 @@ def test_profile_parameters_away_from_the_defaults(env, kw):
     run_both(env, ragged_workload("f32", 1), 4, **kw)
 
 
+def test_caller_supplied_distortion_and_structure_residual(env):
+    """C_raw / F_raw arrays take the place of the computed Eq. 6 / Eq. 7 values (also when theta is given);
+    compute_F = False leaves F at 0."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload("f32", 64)
+    params = binding.default_profile_params()
+    prof = binding.Profiler(w.blocks, params)
+    orc = OracleRunner(w.blocks, None, **oracle_params(params))
+    buf = device.new_buffer(w)
+    for t in range(1, 4):
+        device.fill(w, buf, 21, t)
+        prof.step(buf)
+        orc.step_from_device(buf)
+    n = len(w.blocks)
+    rng = np.random.default_rng(3)
+    C_raw, F_raw = rng.random(n) * 2.0, rng.random(n)
+    theta = torch.randn(w.buffer_numel, device="cuda:0")
+    stats, risk = prof.finalize(w.configs, C_raw=C_raw, F_raw=F_raw, theta=theta)
+    rp = oracle.default_risk_params()
+    for i in range(n):
+        want = orc.state[i].finalize(rp, C_raw=float(C_raw[i]), F_raw=float(F_raw[i]))
+        assert stats[i].C == C_raw[i] and stats[i].F == F_raw[i]
+        assert_stats_close(stats[i], want, f"supplied C, F block {i}")
+        assert_risk_close(risk[i], np.array([oracle.phi(want, c, False, rp) for c in w.configs]), f"block {i}")
+    stats, _ = prof.finalize(w.configs, compute_F=False)
+    assert all(stats[i].F == 0.0 and stats[i].s_F == 0.0 and stats[i].C == 0.0 for i in range(n))
+
+
 def test_other_blocks_do_not_matter(env):
     torch, binding = env["torch"], env["binding"]
     blocks = [(0, 5000), (5003, 777), (6000, 30000)]
