@@ -139,6 +139,25 @@ def test_full_candidate_space_with_soft_preference(env):
     assert_risk_close(risk, orisk, "k21")
 
 
+@pytest.mark.parametrize("kw", [dict(A_low=0.8 * np.log(2.0), A_high=1.2 * np.log(10.0)), dict(A_low=1.2 * np.log(2.0), A_high=0.8 * np.log(10.0)),
+                                dict(rho_low=0.0, rho_high=1.0, eta_low=-1.0, eta_high=4.0), dict(use_snr_gate=0, gamma=0.0), dict(gamma=1.0)])
+def test_risk_parameters_away_from_the_defaults(env, kw):
+    """Anchors of App. A moved (the +-20 % of the paper's anchor study among them), SNR gate off, other gamma."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload("f32", 64)
+    prof = binding.Profiler(w.blocks)
+    orc = OracleRunner(w.blocks, **oracle_params(prof.params))
+    buf = device.new_buffer(w)
+    for t in range(1, 5):
+        device.fill(w, buf, 8, t); prof.step(buf); orc.step_from_device(buf)
+    theta = torch.randn(w.buffer_numel, device="cuda:0")
+    stats, risk = prof.finalize(w.configs, risk_params=binding.default_risk_params(**kw), theta=theta)
+    ostats, orisk = orc.finalize(w.configs, rp=oracle.default_risk_params(**kw), shapes=[(b.rows, b.cols) for b in w.blocks], theta=theta)
+    for i in range(len(w.blocks)):
+        assert_stats_close(stats[i], ostats[i], f"block {i}")
+    assert_risk_close(risk, orisk, str(kw))
+
+
 def test_dirty_workspace_and_windows_back_to_back(env):
     """begin must not depend on what the workspace held: it is filled with 0xFF bytes (NaN patterns) first,
     then reused for a second window after end; finalize in the middle of a window leaves the window intact."""
