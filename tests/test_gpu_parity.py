@@ -158,6 +158,30 @@ def test_risk_parameters_away_from_the_defaults(env, kw):
     assert_risk_close(risk, orisk, str(kw))
 
 
+def test_steps_and_finalize_on_a_side_stream(env):
+    """Generation, step and finalize are ordered by one non-default stream alone (default priority)."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload("bf16", 64)
+    params = binding.default_profile_params(grad_dtype=1)
+    side = torch.cuda.Stream()
+    bufs = [device.new_buffer(w) for _ in range(4)]
+    torch.cuda.synchronize()
+    prof = binding.Profiler(w.blocks, params)
+    with torch.cuda.stream(side):
+        for t, buf in enumerate(bufs, start=1):
+            device.fill(w, buf, 31, t)                   # launched on the current (side) stream
+            prof.step(buf, stream=side)
+        stats, risk = prof.finalize(w.configs, stream=side)
+    side.synchronize()
+    orc = OracleRunner(w.blocks, None, **oracle_params(params))
+    for buf in bufs:
+        orc.step_from_device(buf)
+    ostats, orisk = orc.finalize(w.configs, shapes=[(b.rows, b.cols) for b in w.blocks])
+    for i in range(len(w.blocks)):
+        assert_stats_close(stats[i], ostats[i], f"side stream block {i}")
+    assert_risk_close(risk, orisk, "side stream")
+
+
 def test_dirty_workspace_and_windows_back_to_back(env):
     """begin must not depend on what the workspace held: it is filled with 0xFF bytes (NaN patterns) first,
     then reused for a second window after end; finalize in the middle of a window leaves the window intact."""
