@@ -35,3 +35,38 @@ def test_fullsize_sampled_blocks(env, name, T):  # noqa: F811
     torch = env["torch"]
     run_both(env, w, T, only=only, check_state=True,
              theta_dtype=torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32)
+
+
+def test_blocks_beyond_2_to_the_31_coordinates(env):  # noqa: F811
+    """One vector block and one matrix block of more than 2^31 coordinates each, fed a constant gradient: the
+    intensive statistics equal those of a small oracle block on the same gradient and the extensive ones scale
+    with d exactly (no coordinate skipped or counted twice where 32-bit indices would wrap)."""
+    import oracle
+    from helpers import oracle_params
+    torch, binding = env["torch"], env["binding"]
+    d_vec = (1 << 31) + (1 << 29) + 12_345
+    rows, cols = 40_000, 60_001                                   # 2,400,040,000 > 2^31, cols not a multiple of 4
+    off_mat = (d_vec + 63) // 64 * 64
+    blocks = [(0, d_vec), (off_mat, rows * cols, rows, cols)]
+    n = off_mat + rows * cols
+    c = 0.375                                                     # exact in bf16
+    params = binding.default_profile_params(grad_dtype=1)
+    g = torch.full((n,), c, dtype=torch.bfloat16, device="cuda:0")
+    theta = torch.full((n,), 0.5, dtype=torch.bfloat16, device="cuda:0")
+    prof = binding.Profiler(blocks, params)
+    small = oracle.Block(1000, **oracle_params(params))
+    gs = np.full(1000, (np.float32(c).view(np.uint32) >> 16).astype(np.uint16), dtype=np.uint16)
+    for _ in range(3):
+        prof.step(g)
+        small.step(gs)
+    stats, _ = prof.finalize(theta=theta)
+    want = small.finalize()
+    for i, d in enumerate((d_vec, rows * cols)):
+        st = stats[i]
+        assert st.numel == d and st.steps == 3 and st.n_cos == 2
+        assert st.A == 0.0 and st.q10 == want.q10 and st.q90 == want.q90
+        assert abs(st.F) <= 1e-6 and abs(st.C) <= 1e-6
+        for f in ("rho_bar", "snr", "Q16", "Q8", "err_m16", "err_v16", "err_m8", "err_v8"):
+            assert getattr(st, f) == pytest.approx(getattr(want, f), rel=1e-5, abs=1e-7), f
+        for f in ("m_sq", "v_l1", "g_sq_last"):
+            assert getattr(st, f) == pytest.approx(getattr(want, f) * d / 1000.0, rel=1e-6), f
