@@ -10,6 +10,8 @@
  *   baoc_profile_step      feed one sampled gradient g_t (one fused HBM pass)
  *   baoc_profile_finalize  per-block metrics z_i and the risk table Phi[i][c]
  *   baoc_allocate          exact solution of the allocation problem (Eq. 2)
+ *   baoc_sample_*          optional front end: fixed index sets Omega_i and a gather (Sec. 3.1)
+ *   baoc_partition         block partitioning over structural units (App. C.2, Algorithm 2)
  *
  * Conventions
  *   - Every function returns a status (BAOC_OK = 0, errors negative).  On an
@@ -19,7 +21,8 @@
  *   - The caller owns every buffer it passes in, including the device
  *     workspace; the library owns only the opaque handle.
  *   - A handle is not thread safe; different handles are independent.
- *   - Every coordinate of a block is profiled (Omega_i = all of B_i).
+ *   - The profiler takes every coordinate of the blocks it is given (Omega_i = all of B_i);
+ *     to profile a subset, gather it first (baoc_sample_*) and describe the compact buffer.
  */
 #ifndef BAOC_H
 #define BAOC_H
@@ -45,7 +48,8 @@ extern "C" {
 /* One parameter block B_i (Sec. 3.1): numel = d_i coordinates starting `offset`
  * elements into the flat gradient buffer.  Blocks may come in any order and
  * leave gaps but must not overlap.  rows*cols == numel marks a matrix block
- * (reserved for the structure residual of Eq. 7); otherwise both are 0. */
+ * (its v-hat, viewed as rows x cols row-major, enters the structure residual of Eq. 7);
+ * otherwise both are 0. */
 typedef struct {
     uint64_t offset;
     uint64_t numel;
