@@ -240,3 +240,22 @@ def test_traffic_file_is_read_per_workload():
     u = bench.read_traffic(path, "unet")
     assert u is not None and 1.0 <= u / (28 * 859520964) < 1.02
     assert bench.read_traffic(path, "resnet50") is None and bench.read_traffic(path + ".missing", "llama7b") is None
+
+
+def test_host_entry_points_under_address_and_ub_sanitizers(tmp_path):
+    """baoc_allocate and baoc_partition (host code only) built with g++ -fsanitize=address,undefined and driven
+    with random instances: NaN / infinite risks, exclusions, tight and slack budgets, node limits."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = os.path.join(root, "paper_2605_04711_amd", "csrc")
+    exe = str(tmp_path / "fuzz_host")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-static-libasan", "-fno-sanitize-recover=undefined",
+           "-I", os.path.join(root, "include"), "-I", src, "-o", exe, os.path.join(root, "tests", "fuzz_host.cpp")]
+    cmd += [os.path.join(src, f) for f in ("baoc_allocate.cpp", "baoc_partition.cpp", "baoc_risk.cpp")]
+    subprocess.run(cmd, check=True, capture_output=True, timeout=300)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "allocate: ok" in r.stdout and "partition: ok 400" in r.stdout and "runtime error" not in r.stderr
