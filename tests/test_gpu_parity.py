@@ -182,6 +182,31 @@ def test_steps_and_finalize_on_a_side_stream(env):
     assert_risk_close(risk, orisk, "side stream")
 
 
+@pytest.mark.parametrize("dtype,shape", [("f32", dict()), ("bf16", dict()), ("bf16", dict(chunk_groups=3, groups_per_wave=2)),
+                                         ("f32", dict(chunk_groups=20, groups_per_wave=1))])
+def test_nothing_is_written_outside_the_workspace(env, dtype, shape):
+    """Guard bands of 1 MiB before and after the workspace (and after the gradient and parameter buffers) keep
+    their pattern through begin, steps and finalize with F and C."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload(dtype, 3)
+    params = binding.default_profile_params(grad_dtype=1 if dtype == "bf16" else 0, **shape)
+    nbytes = binding.workspace_bytes(w.blocks, params)
+    band = 1 << 20
+    arena = torch.full((band + nbytes + band,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gbuf = torch.full((w.buffer_numel + band,), 1.0, dtype=tdt, device="cuda:0")
+    theta = torch.full((w.buffer_numel + band,), 0.5, dtype=tdt, device="cuda:0")
+    prof = binding.Profiler(w.blocks, params, workspace=arena[band:band + nbytes])
+    for t in range(1, 4):
+        device.fill(w, gbuf[:w.buffer_numel], 13, t)
+        prof.step(gbuf[:w.buffer_numel])
+    prof.finalize(w.configs, theta=theta[:w.buffer_numel])
+    torch.cuda.synchronize()
+    assert bool((arena[:band] == 0xA5).all()) and bool((arena[band + nbytes:] == 0xA5).all())
+    assert bool((gbuf[w.buffer_numel:] == 1.0).all()) and bool((theta[w.buffer_numel:] == 0.5).all())
+    prof.close()
+
+
 def test_dirty_workspace_and_windows_back_to_back(env):
     """begin must not depend on what the workspace held: it is filled with 0xFF bytes (NaN patterns) first,
     then reused for a second window after end; finalize in the middle of a window leaves the window intact."""

@@ -44,6 +44,30 @@ def test_index_sets_gather_and_sampled_statistics(env, dtype, ratio):  # noqa: F
         assert_stats_close(stats[i], orc[i].finalize(), f"sampled block {i} ratio {ratio}")
 
 
+def test_sampler_writes_stay_inside_its_buffers(env):  # noqa: F811
+    torch, binding = env["torch"], env["binding"]
+    w = ragged_workload("bf16", 1)
+    blocks = [(b.offset, b.numel) for b in w.blocks]
+    lib = binding.load_library()
+    import ctypes as C
+    arr = binding._block_array(blocks)
+    compact = (binding.Block * len(blocks))()
+    cn, wb = C.c_uint64(), C.c_uint64()
+    assert lib.baoc_sample_layout(arr, len(blocks), 0.37, compact, C.byref(cn), C.byref(wb)) == 0
+    band = 1 << 16
+    arena = torch.full((band + wb.value + band,), 0x5A, dtype=torch.uint8, device="cuda:0")
+    h = C.c_void_p()
+    assert lib.baoc_sample_begin(arr, len(blocks), 0.37, 99, arena.data_ptr() + band, wb.value, C.byref(h)) == 0
+    g = torch.randn(w.buffer_numel, device="cuda:0").to(torch.bfloat16)
+    out = torch.full((cn.value + band,), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.baoc_sample_gather(h, g.data_ptr(), g.numel(), binding.GRAD_BF16, out.data_ptr(), cn.value, st) == 0
+    torch.cuda.synchronize()
+    assert bool((arena[:band] == 0x5A).all()) and bool((arena[band + wb.value:] == 0x5A).all())
+    assert bool((out[cn.value:] == 7.0).all())
+    lib.baoc_sample_end(h)
+
+
 def test_sampler_rejects_bad_arguments(env):  # noqa: F811
     torch, binding = env["torch"], env["binding"]
     for ratio in (0.0, -0.1, 1.5, float("nan")):
