@@ -31,7 +31,9 @@ def parse():
     ap.add_argument("--workload", default="llama7b")
     ap.add_argument("--ring", type=int, default=4, help="distinct pre-generated gradient buffers cycled through")
     ap.add_argument("--chunk-groups", type=int, default=0, help="launch shape of the step kernel, 0 = library default")
+    ap.add_argument("--chunk-slices", type=int, default=0)
     ap.add_argument("--groups-per-wave", type=int, default=0)
+    ap.add_argument("--waves-per-workgroup", type=int, default=0)
     ap.add_argument("--resident-workgroups", type=int, default=0)
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -162,7 +164,8 @@ def main():
     K = a.steps or w.T
     D = w.numel
     params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0, chunk_groups=a.chunk_groups,
-                                            groups_per_wave=a.groups_per_wave, resident_workgroups=a.resident_workgroups)
+                                            chunk_slices=a.chunk_slices, groups_per_wave=a.groups_per_wave,
+                                            waves_per_workgroup=a.waves_per_workgroup, resident_workgroups=a.resident_workgroups)
     mem, tc, b_mem, cap = W.allocation_inputs(w)
     cap = 1e12 if not np.isfinite(cap) else cap
 
@@ -232,8 +235,8 @@ def main():
         "config": {"workload": f"{w.name}: {len(w.blocks)} blocks, {D:,} coordinates, {w.grad_dtype} gradients, "
                                f"fp32 EMA states, window of {K} steps + finalize + allocate (K={len(w.configs)} configurations)",
                    "blocks": len(w.blocks), "coordinates": D, "grad_dtype": w.grad_dtype, "window_steps": K,
-                   "gradient_ring": R, "workspace_bytes": nbytes, "launch_shape": {"chunk_groups": a.chunk_groups or "default", "groups_per_wave": a.groups_per_wave or "default",
-                                    "resident_workgroups": a.resident_workgroups or "default"}},
+                   "gradient_ring": R, "workspace_bytes": nbytes, "launch_shape": {k: (getattr(a, k) or "default") for k in ("chunk_groups", "chunk_slices", "groups_per_wave",
+                                                                                        "waves_per_workgroup", "resident_workgroups")}},
         "breakdown_ms": {"begin": round(r["begin"] * 1e3, 3), "first_step": round(step_ms[0], 4), "step_avg": round(avg_ms, 4),
                          "step_min": round(min(steady), 4), "finalize": round(finalize_ms, 3),
                          "allocate": round(r["allocate"] * 1e3, 3)},

@@ -65,14 +65,18 @@ typedef struct {
     float    eps_update;   /* epsilon inside u = m / (sqrt(v) + eps_update), Eq. 8 (1e-8); > 0 */
     uint32_t quant_block;  /* coordinates per 8-bit absmax group; only 256 is built     */
     uint32_t grad_dtype;   /* BAOC_GRAD_F32 | BAOC_GRAD_BF16 (states are always fp32)   */
-    /* Launch shape of the per-step kernel; 0 = the default measured best for the gradient type.
-     * None of the three changes any result bit except through the order of the partial sums. */
-    uint32_t chunk_groups;        /* quantisation groups per workgroup (default 4 * groups_per_wave)  */
-    uint32_t groups_per_wave;     /* adjacent groups a wavefront loads together: 1 or 2
-                                   * (default 2 for bf16 gradients, 1 for fp32)                       */
+    /* Launch shape of the per-step kernel; 0 = the default measured best for the gradient type
+     * (fp32 layouts of fewer than 2^26 coordinates: 4 wavefronts x 1 group, 4 resident).
+     * None of the five changes any result bit except through the order of the partial sums. */
+    uint32_t chunk_groups;        /* quantisation groups per chunk, the unit of the tables and of the
+                                   * finalize passes (default 8 for bf16 gradients, 4 for fp32)       */
+    uint32_t chunk_slices;        /* workgroups of the step kernel per chunk (default: as many as
+                                   * make a slice one round, chunk_groups / (waves * groups_per_wave)) */
+    uint32_t groups_per_wave;     /* adjacent groups a wavefront loads together: 1 or 2 (default 2)   */
+    uint32_t waves_per_workgroup; /* 1, 2 or 4 (default 4 for bf16 gradients, 1 for fp32)             */
     uint32_t resident_workgroups; /* workgroups of the steady-state step kernel resident per compute
-                                   * unit, 3..8, held by launching with unused LDS; 8 = no limit
-                                   * (default 3 for bf16 gradients, 4 for fp32)                       */
+                                   * unit, 3..32, held by launching with unused LDS (default 3 for
+                                   * bf16 gradients, 10 for fp32)                                     */
 } baoc_profile_params;
 
 /* A candidate configuration c = (y_a, y_m, y_d, y_f, b) of Def. 3.1:

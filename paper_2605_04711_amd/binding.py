@@ -23,7 +23,8 @@ class Block(C.Structure):
 class ProfileParams(C.Structure):
     _fields_ = [("beta_m", C.c_float), ("beta_v", C.c_float), ("beta_rho", C.c_double), ("eps", C.c_double),
                 ("eps_update", C.c_float), ("quant_block", C.c_uint32), ("grad_dtype", C.c_uint32),
-                ("chunk_groups", C.c_uint32), ("groups_per_wave", C.c_uint32), ("resident_workgroups", C.c_uint32)]
+                ("chunk_groups", C.c_uint32), ("chunk_slices", C.c_uint32), ("groups_per_wave", C.c_uint32),
+                ("waves_per_workgroup", C.c_uint32), ("resident_workgroups", C.c_uint32)]
 
 
 class Config(C.Structure):

@@ -10,12 +10,15 @@ namespace baoc {
 constexpr uint32_t kQB = 256;            // coordinates per 8-bit absmax group = one wavefront x 4
 constexpr uint32_t kNumSums = 16;        // floats in one partial-sum row
 
-// Launch shape of the step kernel, per gradient type (fp32, bf16): adjacent groups a wavefront
-// loads together and workgroups resident per compute unit.  Measured: a DRAM stream of 4 reads and
-// 3 writes per coordinate runs fastest with few, fat requesters; more resident wavefronts only add
-// row conflicts.  A chunk is one round of a workgroup (4 wavefronts x groups_per_wave groups).
-constexpr uint32_t kDefaultGroupsPerWave[2] = {1, 2};
-constexpr uint32_t kDefaultResidentWorkgroups[2] = {4, 3};
+// Launch shape of the step kernel, per gradient type (fp32, bf16).  Measured: a DRAM stream of 4 reads
+// and 3 writes per coordinate runs fastest with few, fat requesters; more resident wavefronts only add
+// row conflicts.  fp32 gradients: single-wavefront workgroups of two adjacent groups, about 10 resident
+// per compute unit; bf16: 4 wavefronts x 2 groups, 3 resident.  A chunk (the unit of the tables and of
+// the finalize passes) is cut into slices of one round each.
+struct LaunchShape { uint32_t chunk_groups, groups_per_wave, waves_per_workgroup, resident_workgroups; };
+constexpr LaunchShape kDefaultShape[2] = {{4, 2, 1, 10}, {8, 2, 4, 3}};
+constexpr LaunchShape kSmallF32Shape = {4, 1, 4, 4};          // fp32 layouts below kSmallLayout coordinates
+constexpr uint64_t kSmallLayout = 1ull << 26;
 constexpr uint32_t kLdsBytesPerCU = 160 * 1024;   // gfx950
 
 // order of the sums in a partial row and in the per-block raw record

@@ -43,6 +43,7 @@ struct alignas(8) BlockRow {
     uint32_t groups_per_chunk;
     uint32_t vec_first;     // first entry of the block in the list of chunks finalize walks chunk-wise; kNoVec when tiled
     uint32_t first_slab, n_slabs;   // the block's slabs of partial rows (first stage of the per-block sum)
+    uint32_t first_prow, n_prows;   // the block's partial rows of the step kernel (one per workgroup: chunk x slice)
     uint64_t rank[4];       // order statistics wanted from v: lo(0.1), lo+1, lo(0.9), lo+1
 };
 
@@ -182,21 +183,26 @@ template <> struct GradIO<BAOC_GRAD_BF16> {
 // ---------------------------------------------------------------------------
 
 // FIRST: the states are known to be zero (first step after begin), so they are not read.
-// G: quantisation groups a wavefront takes per round, next to each other (G * 1 KB of m and of v per
-// wavefront and round); a workgroup covers 4 * G groups per round.  The loads of a round are issued
-// together, one round ahead of their use.  With the default chunking a chunk is a single round, so no
-// wavefront ever waits on its own stores.
-template <int GT, bool FIRST, int G>
-__global__ __launch_bounds__(256) void k_step(
+// A workgroup of NW wavefronts takes one slice of a chunk (`slice_groups` quantisation groups, `slices`
+// slices per chunk) and writes one partial row.  G: groups a wavefront takes per round, next to each
+// other (G * 1 KB of m and of v per wavefront and round); the workgroup covers NW * G groups per round.
+// The loads of a round are issued together, one round ahead of their use.  With the default shapes a
+// slice is a single round, so no wavefront ever waits on its own stores.
+template <int GT, bool FIRST, int G, int NW>
+__global__ __launch_bounds__(64 * NW) void k_step(
     const typename GradIO<GT>::elem* __restrict__ grad,
     float* __restrict__ m_all, float* __restrict__ v_all,
     typename GradIO<GT>::elem* __restrict__ gp_all,
-    const Chunk* __restrict__ chunks, float* __restrict__ partials, StepConsts k)
+    const Chunk* __restrict__ chunks, float* __restrict__ partials, StepConsts k,
+    uint32_t slices, uint32_t slice_groups)
 {
     typedef GradIO<GT> IO;
-    const Chunk ck = chunks[blockIdx.x];
+    const uint32_t chunk = blockIdx.x / slices, slice = blockIdx.x - chunk * slices;
+    const Chunk ck = chunks[chunk];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t ngroups = (ck.count + (kQB - 1)) / kQB;
+    // this workgroup's groups of the chunk: [g_begin, ngroups)
+    const uint32_t g_begin = slice * slice_groups;
+    const uint32_t ngroups = min((ck.count + (kQB - 1)) / kQB, g_begin + slice_groups);
     const typename IO::elem* gsrc = grad + ck.grad_start;
     const bool vec_ok = (reinterpret_cast<uintptr_t>(gsrc) & IO::kAlignMask) == 0;
 
@@ -221,14 +227,14 @@ __global__ __launch_bounds__(256) void k_step(
             }
         }
     };
-    if (wave * G < ngroups) issue(wave * G);
+    if (g_begin + wave * G < ngroups) issue(g_begin + wave * G);
 
-    for (uint32_t first = wave * G; first < ngroups; first += 4 * G) {
+    for (uint32_t first = g_begin + wave * G; first < ngroups; first += NW * G) {
         f4 cm[G], cv[G];
         GV cp[G], cg[G];
 #pragma unroll
         for (int i = 0; i < G; ++i) { cm[i] = nm[i]; cv[i] = nv[i]; cp[i] = np[i]; cg[i] = ng[i]; }
-        if (first + 4 * G < ngroups) issue(first + 4 * G);
+        if (first + NW * G < ngroups) issue(first + NW * G);
 #pragma unroll
         for (int i = 0; i < G; ++i) {
             const uint32_t grp = first + i;
@@ -340,13 +346,13 @@ __global__ __launch_bounds__(256) void k_step(
         const float keep = b0 ? acc[1] : acc[0], send = b0 ? acc[0] : acc[1];
         acc[0] = keep + dpp<0xB1, 0xf>(0.f, send);       // partner lane ^ 1
     }
-    __shared__ float red[16 * kNumSums];                  // [wavefront * 4 + row][sum]
+    __shared__ float red[NW * 4 * kNumSums];              // [wavefront * 4 + row][sum]
     red[threadIdx.x] = acc[0];
     __syncthreads();
     if (threadIdx.x < kNumSums) {
         float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) s += red[q * kNumSums + threadIdx.x];
+        for (int q = 0; q < NW * 4; ++q) s += red[q * kNumSums + threadIdx.x];
         partials[(uint64_t)blockIdx.x * kNumSums + threadIdx.x] = s;
     }
 }
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(256) void k_step(
 // two stages (slabs of kSlabRows rows by k_slab_reduce, then k_block_reduce); smaller ones directly.
 constexpr uint32_t kSlabRows = 4096;      // partial rows summed by one workgroup of the first stage
 
-struct alignas(8) Slab { uint32_t first_chunk, n_chunks; };
+struct alignas(8) Slab { uint32_t first_row, n_rows; };
 
 // First stage for large blocks: one workgroup adds a slab of partial rows in fp64.
 __global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ partials, const Slab* __restrict__ slabs,
@@ -365,8 +371,8 @@ __global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ p
     double acc[kNumSums];
 #pragma unroll
     for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.0;
-    for (uint32_t c = threadIdx.x; c < sl.n_chunks; c += 256) {
-        const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(sl.first_chunk + c) * kNumSums);
+    for (uint32_t c = threadIdx.x; c < sl.n_rows; c += 256) {
+        const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(sl.first_row + c) * kNumSums);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const f4 t = row[q];
@@ -409,8 +415,8 @@ __global__ __launch_bounds__(256) void k_block_reduce(
         double acc[kNumSums];
 #pragma unroll
         for (int i = 0; i < (int)kNumSums; ++i) acc[i] = 0.0;
-        for (uint32_t c = threadIdx.x; c < br.n_chunks; c += 256) {
-            const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(br.first_chunk + c) * kNumSums);
+        for (uint32_t c = threadIdx.x; c < br.n_prows; c += 256) {
+            const f4* row = reinterpret_cast<const f4*>(partials + (uint64_t)(br.first_prow + c) * kNumSums);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const f4 t = row[q];
@@ -1044,6 +1050,8 @@ using namespace baoc;
 
 struct Plan {
     uint64_t n_chunks = 0;
+    uint32_t gpw = 1, nw = 4, slices = 1, slice_groups = 4, resident = 8;   // launch shape of the step kernel
+    uint64_t n_prows = 0;         // partial rows of the step kernel = n_chunks * slices
     std::vector<BlockRow> rows;
     std::vector<MatRow> mats;     // matrix blocks (rows*cols == numel), for Eq. 7
     uint64_t n_tasks = 0, n_quads = 0, n_vec_chunks = 0;
@@ -1078,8 +1086,10 @@ static int check_params(const baoc_profile_params* p)
     if (!(p->eps >= 0.0) || !(p->eps_update > 0.f)) return BAOC_ERR_INVALID;   // u = m / (sqrt(v) + eps_update) must exist where v = 0
     if (p->grad_dtype != BAOC_GRAD_F32 && p->grad_dtype != BAOC_GRAD_BF16) return BAOC_ERR_INVALID;
     if (p->quant_block != kQB) return BAOC_ERR_UNSUPPORTED;
-    if (p->chunk_groups > 4096 || p->groups_per_wave > 2) return BAOC_ERR_INVALID;
-    if (p->resident_workgroups != 0 && (p->resident_workgroups < 3 || p->resident_workgroups > 8)) return BAOC_ERR_INVALID;
+    if (p->chunk_groups > 4096 || p->groups_per_wave > 2 || p->chunk_slices > 64) return BAOC_ERR_INVALID;
+    if (p->waves_per_workgroup != 0 && p->waves_per_workgroup != 1 && p->waves_per_workgroup != 2 && p->waves_per_workgroup != 4)
+        return BAOC_ERR_INVALID;
+    if (p->resident_workgroups != 0 && (p->resident_workgroups < 3 || p->resident_workgroups > 32)) return BAOC_ERR_INVALID;
     return BAOC_OK;
 }
 
@@ -1105,9 +1115,18 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         if (iv[i - 1].first + iv[i - 1].second > iv[i].first) return BAOC_ERR_INVALID;
     if (max_end) *max_end = end_max;
 
-    const uint32_t gpw = prm->groups_per_wave ? prm->groups_per_wave : kDefaultGroupsPerWave[prm->grad_dtype];
-    const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : 4 * gpw;
     Plan& P = *out;
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < n; ++i) total += blocks[i].numel;
+    // fp32 layouts too small to keep the chip busy for long (ResNet-50-sized) run faster with the 4-wavefront shape
+    const LaunchShape& ds = (prm->grad_dtype == BAOC_GRAD_F32 && total < kSmallLayout) ? kSmallF32Shape : kDefaultShape[prm->grad_dtype];
+    P.gpw = prm->groups_per_wave ? prm->groups_per_wave : ds.groups_per_wave;
+    P.nw = prm->waves_per_workgroup ? prm->waves_per_workgroup : ds.waves_per_workgroup;
+    P.resident = prm->resident_workgroups ? prm->resident_workgroups : ds.resident_workgroups;
+    const uint32_t round = P.gpw * P.nw;                            // groups a workgroup takes per round
+    const uint32_t cg = prm->chunk_groups ? prm->chunk_groups : std::max(ds.chunk_groups, round);
+    P.slices = prm->chunk_slices ? std::min(prm->chunk_slices, cg) : std::max(1u, cg / round);   // default: one round per slice
+    P.slice_groups = (cg + P.slices - 1) / P.slices;
     P.n_chunks = 0; P.rows.resize(n); P.slabs.clear();
     uint64_t state = 0;
     for (uint32_t i = 0; i < n; ++i) {
@@ -1120,10 +1139,13 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         r.first_chunk = (uint32_t)P.n_chunks;
         r.n_chunks = (uint32_t)((groups + per - 1) / per);
         r.groups_per_chunk = (uint32_t)per; r.vec_first = 0;
+        const uint64_t prows = (uint64_t)r.n_chunks * P.slices, first_prow = P.n_chunks * P.slices;
+        if (first_prow + prows > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
+        r.first_prow = (uint32_t)first_prow; r.n_prows = (uint32_t)prows;
         r.first_slab = (uint32_t)P.slabs.size();
-        if (r.n_chunks > kSlabRows)                                  // small blocks are summed directly
-            for (uint32_t c = 0; c < r.n_chunks; c += kSlabRows)
-                P.slabs.push_back(Slab{r.first_chunk + c, std::min(kSlabRows, r.n_chunks - c)});
+        if (r.n_prows > kSlabRows)                                   // small blocks are summed directly
+            for (uint32_t c = 0; c < r.n_prows; c += kSlabRows)
+                P.slabs.push_back(Slab{r.first_prow + c, std::min(kSlabRows, r.n_prows - c)});
         r.n_slabs = (uint32_t)P.slabs.size() - r.first_slab;
         P.n_chunks += r.n_chunks;
         for (int q = 0; q < 2; ++q) {                                // ranks bracketing position q (d-1)
@@ -1136,6 +1158,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         if (P.n_chunks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
     }
     P.padded = state;
+    P.n_prows = P.n_chunks * P.slices;
     // Finalize walks blocks with a real matrix shape tile-wise and the rest chunk-wise.  A shape with a
     // single row or column is rank one by construction (F = 0 exactly) and stays on the chunk path.
     P.mats.clear(); P.n_tasks = 0; P.n_quads = 0; P.n_vec_chunks = 0;
@@ -1166,7 +1189,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_m = o;        o = align_up(o + P.padded * 4, 256);
     P.off_v = o;        o = align_up(o + P.padded * 4, 256);
     P.off_gp = o;       o = align_up(o + P.padded * gsz, 256);
-    P.off_partials = o; o = align_up(o + P.n_chunks * kNumSums * 4, 256);
+    P.off_partials = o; o = align_up(o + P.n_prows * kNumSums * 4, 256);   // also holds the per-chunk sums of Eq. 6
     P.off_chunks = o;   o = align_up(o + P.n_chunks * sizeof(Chunk), 256);
     P.off_rows = o;     o = align_up(o + (uint64_t)n * sizeof(BlockRow), 256);
     P.off_rec = o;      o = align_up(o + (uint64_t)n * kRecDoubles * 8, 256);
@@ -1189,12 +1212,29 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     return BAOC_OK;
 }
 
+template <int GT, bool FIRST, int G, int NW>
+static void launch_step_as(uint32_t grid, uint32_t lds, hipStream_t st, const typename GradIO<GT>::elem* g, float* m, float* v,
+                           typename GradIO<GT>::elem* gp, const Chunk* ch, float* part, StepConsts k, uint32_t slices, uint32_t slice_groups)
+{
+    hipLaunchKernelGGL((k_step<GT, FIRST, G, NW>), dim3(grid), dim3(64 * NW), lds, st, g, m, v, gp, ch, part, k, slices, slice_groups);
+}
+
+// The instantiation for (first step?, groups per wavefront, wavefronts per workgroup); the values were validated at begin.
+template <int GT, typename... Args>
+static void launch_step(bool first, uint32_t gpw, uint32_t nw, Args... a)
+{
+#define BAOC_STEP_CASE(GG, NN) \
+    if (gpw == GG && nw == NN) { if (first) launch_step_as<GT, true, GG, NN>(a...); else launch_step_as<GT, false, GG, NN>(a...); return; }
+    BAOC_STEP_CASE(1, 1) BAOC_STEP_CASE(2, 1) BAOC_STEP_CASE(1, 2) BAOC_STEP_CASE(2, 2) BAOC_STEP_CASE(1, 4) BAOC_STEP_CASE(2, 4)
+#undef BAOC_STEP_CASE
+}
+
 extern "C" void baoc_profile_params_default(baoc_profile_params* p)
 {
     if (!p) return;
     p->beta_m = 0.9f; p->beta_v = 0.999f; p->beta_rho = 0.9; p->eps = 1e-12; p->eps_update = 1e-8f;
     p->quant_block = kQB; p->grad_dtype = BAOC_GRAD_F32;
-    p->chunk_groups = 0; p->groups_per_wave = 0; p->resident_workgroups = 0;
+    p->chunk_groups = 0; p->chunk_slices = 0; p->groups_per_wave = 0; p->waves_per_workgroup = 0; p->resident_workgroups = 0;
 }
 
 extern "C" int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
@@ -1258,28 +1298,20 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
     float* v = reinterpret_cast<float*>(h->ws + P.off_v);
     const Chunk* ch = reinterpret_cast<const Chunk*>(h->ws + P.off_chunks);
     float* part = reinterpret_cast<float*>(h->ws + P.off_partials);
-    const uint32_t grid = (uint32_t)P.n_chunks;
     const bool first = h->steps == 0;
-    const uint32_t gpw = q.groups_per_wave ? q.groups_per_wave : kDefaultGroupsPerWave[q.grad_dtype];
     // The first launch is bound by its arithmetic and runs at full residency.  Later launches are bound
-    // by DRAM and run with fewer resident workgroups: each is given so much unused LDS that only
+    // by DRAM and run with fewer resident workgroups: each is given so much unused LDS that only about
     // `resident` of them fit a compute unit (allocations are counted in multiples of 2 KB here).
-    const uint32_t resident = q.resident_workgroups ? q.resident_workgroups : kDefaultResidentWorkgroups[q.grad_dtype];
+    const uint32_t static_lds = P.nw * 4 * kNumSums * 4;
     uint32_t lds = 0;
-    if (!first && resident < 8) lds = kLdsBytesPerCU / resident / 2048 * 2048 - kNumSums * 16 * 4;
-    if (q.grad_dtype == BAOC_GRAD_F32) {
-        float* gp = reinterpret_cast<float*>(h->ws + P.off_gp);
-        const float* g = static_cast<const float*>(d_grad_flat);
-        auto kern = gpw == 2 ? (first ? k_step<BAOC_GRAD_F32, true, 2> : k_step<BAOC_GRAD_F32, false, 2>)
-                             : (first ? k_step<BAOC_GRAD_F32, true, 1> : k_step<BAOC_GRAD_F32, false, 1>);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g, m, v, gp, ch, part, k);
-    } else {
-        uint16_t* gp = reinterpret_cast<uint16_t*>(h->ws + P.off_gp);
-        const uint16_t* g = static_cast<const uint16_t*>(d_grad_flat);
-        auto kern = gpw == 2 ? (first ? k_step<BAOC_GRAD_BF16, true, 2> : k_step<BAOC_GRAD_BF16, false, 2>)
-                             : (first ? k_step<BAOC_GRAD_BF16, true, 1> : k_step<BAOC_GRAD_BF16, false, 1>);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g, m, v, gp, ch, part, k);
-    }
+    if (!first && P.resident * P.nw < 32) lds = kLdsBytesPerCU / P.resident / 2048 * 2048 - static_lds;
+    const uint32_t grid = (uint32_t)P.n_prows;
+    if (q.grad_dtype == BAOC_GRAD_F32)
+        launch_step<BAOC_GRAD_F32>(first, P.gpw, P.nw, grid, lds, st, static_cast<const float*>(d_grad_flat), m, v,
+                                   reinterpret_cast<float*>(h->ws + P.off_gp), ch, part, k, P.slices, P.slice_groups);
+    else
+        launch_step<BAOC_GRAD_BF16>(first, P.gpw, P.nw, grid, lds, st, static_cast<const uint16_t*>(d_grad_flat), m, v,
+                                    reinterpret_cast<uint16_t*>(h->ws + P.off_gp), ch, part, k, P.slices, P.slice_groups);
     h->steps += 1;
     double* slab_sums = reinterpret_cast<double*>(h->ws + P.off_slabsums);
     if (!P.slabs.empty())

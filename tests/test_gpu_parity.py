@@ -96,12 +96,23 @@ def test_ragged_blocks_unaligned_offsets_gaps_and_order(env, dtype, pad, chunk_g
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("groups_per_wave,chunk_groups,resident", [(1, 0, 8), (2, 0, 3), (2, 3, 5), (1, 9, 0), (2, 20, 0), (2, 1, 4)])
-def test_launch_shapes_leave_the_results_alone(env, dtype, groups_per_wave, chunk_groups, resident):
-    """Chunks of one round and of several, whole and partial rounds, one or two groups per wavefront,
-    limited and unlimited residency: the same statistics and bit-identical states."""
-    run_both(env, ragged_workload(dtype, 1), 4, chunk_groups=chunk_groups, groups_per_wave=groups_per_wave,
-             resident_workgroups=resident, theta_dtype=env["torch"].float32)
+@pytest.mark.parametrize("shape", [
+    dict(groups_per_wave=1, waves_per_workgroup=4, resident_workgroups=8),
+    dict(groups_per_wave=2, waves_per_workgroup=4, resident_workgroups=3),
+    dict(groups_per_wave=2, waves_per_workgroup=4, chunk_groups=3, resident_workgroups=5),
+    dict(groups_per_wave=1, waves_per_workgroup=4, chunk_groups=9),                      # several rounds per slice
+    dict(groups_per_wave=2, waves_per_workgroup=4, chunk_groups=20, chunk_slices=1),     # 8 + 8 + 4 groups
+    dict(groups_per_wave=2, waves_per_workgroup=4, chunk_groups=1, resident_workgroups=4),
+    dict(groups_per_wave=2, waves_per_workgroup=1, chunk_groups=4, resident_workgroups=10),
+    dict(groups_per_wave=1, waves_per_workgroup=1, chunk_groups=7, chunk_slices=3, resident_workgroups=32),   # slices of 3, 3, 1
+    dict(groups_per_wave=2, waves_per_workgroup=2, chunk_groups=16, chunk_slices=16),    # slices shorter than a round
+    dict(groups_per_wave=1, waves_per_workgroup=2, chunk_groups=5, chunk_slices=64, resident_workgroups=16),
+])
+def test_launch_shapes_leave_the_results_alone(env, dtype, shape):
+    """Chunks of one slice and of several, slices of one round, of several and of a partial one, one or two groups
+    per wavefront, 1, 2 or 4 wavefronts per workgroup, limited and unlimited residency: the same statistics and
+    bit-identical states."""
+    run_both(env, ragged_workload(dtype, 1), 4, theta_dtype=env["torch"].float32, **shape)
 
 
 def test_resnet50_all_blocks_all_steps(env):

@@ -68,7 +68,9 @@ def test_layout_validation():
     assert status([(0, 10)], groups_per_wave=3) == binding.ERR_INVALID
     assert status([(0, 10)], eps_update=0.0) == binding.ERR_INVALID            # u must exist where v = 0
     assert status([(0, 10)], resident_workgroups=2) == binding.ERR_INVALID
-    assert status([(0, 10)], resident_workgroups=9) == binding.ERR_INVALID
+    assert status([(0, 10)], resident_workgroups=33) == binding.ERR_INVALID
+    assert status([(0, 10)], waves_per_workgroup=3) == binding.ERR_INVALID
+    assert status([(0, 10)], chunk_slices=65) == binding.ERR_INVALID
     assert status([(0, 10)], chunk_groups=5000) == binding.ERR_INVALID
     assert status([(0, 1 << 33)]) == binding.ERR_UNSUPPORTED
     assert status([]) == binding.ERR_INVALID
