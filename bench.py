@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--sample-ratio", type=float, default=0.0,
                     help="sparse coordinate sampling (Sec. 3.1): gather g[Omega] with this ratio before every step and profile "
                          "the compact buffer; prints its own JSON line (not the headline metric)")
+    ap.add_argument("--memory-probe", action="store_true",
+                    help="instead of the benchmark: pure streams with the step kernel's traffic mix (no arithmetic), read-only and "
+                         "write-only, at several residencies -- what this HBM system delivers; prints its own JSON line")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "k_step_pmc_traffic.txt"))
     return ap.parse_args()
 
@@ -144,6 +147,42 @@ def sampled_windows(a, w, ring, theta, params, mem, tc, b_mem, cap):
                          "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": g_avg, "launches": len(g_ms)}}
 
 
+def memory_probe(coordinates, dev):
+    """Pure streams of the bf16 step kernel's bytes (22 per coordinate: 4 reads, 3 writes), of reads and of writes alone."""
+    import torch
+    from synth import device
+    L = device.probe_lib()
+    n = coordinates // 4096 * 4096
+    m = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros_like(m)
+    gp = torch.zeros(n, dtype=torch.bfloat16, device=dev); g = torch.zeros_like(gp)
+    sink = torch.zeros(256, dtype=torch.float32, device=dev)
+    st = torch.cuda.current_stream(dev).cuda_stream
+
+    def run(kind, waves, groups, resident):
+        lds = 0 if not resident else 160 * 1024 // resident // 2048 * 2048        # unused LDS that limits the residency
+        def launch():
+            rc = L.synth_mem_probe(kind, waves, groups, lds, n, m.data_ptr(), v.data_ptr(), gp.data_ptr(), g.data_ptr(), sink.data_ptr(), st)
+            if rc:
+                raise RuntimeError(f"synth_mem_probe: {rc}")
+        launch(); torch.cuda.synchronize()
+        ms = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); launch(); e1.record(); e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        t = sorted(ms)[2]
+        nbytes = (22 if kind == 0 else 4) * n
+        return {"stream": ("mix 4r3w", "read", "write")[kind], "waves_per_workgroup": waves, "groups_per_wave": groups,
+                "resident_workgroups": resident or "unlimited", "waves_per_cu": (resident * waves) if resident else "max",
+                "ms": round(t, 3), "GB/s": round(nbytes / t / 1e6)}
+
+    rows = [run(1, 4, 1, 0), run(1, 4, 2, 0), run(2, 4, 1, 0), run(2, 4, 2, 0)]
+    for waves, groups, resident in [(4, 1, 0), (4, 2, 0), (4, 2, 4), (4, 2, 3), (2, 2, 8), (2, 2, 4), (2, 2, 3), (1, 2, 16), (1, 2, 10),
+                                    (1, 2, 6), (1, 2, 4), (1, 4, 8), (1, 4, 4), (1, 4, 3), (4, 1, 0)]:
+        rows.append(run(0, waves, groups, resident))
+    return {"metric": "memory-system probe", "unit": "GB/s", "peak": HBM_PEAK_GBS, "coordinates": n, "rows": rows}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -160,6 +199,9 @@ def main():
         sys.exit(2)
     B.load_library(); device.lib()
     dev = torch.device("cuda:0")
+    if a.memory_probe:
+        print(json.dumps(memory_probe(W.make(a.workload, seed=a.seed).numel, dev)))
+        return
     w = W.make(a.workload, seed=a.seed)
     K = a.steps or w.T
     D = w.numel

@@ -11,7 +11,28 @@ LIB = os.path.join(_HERE, "libbaoc_gradgen.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
+PROBE_SRC = os.path.join(_HERE, "csrc", "memprobe.hip")
+PROBE_LIB = os.path.join(_HERE, "libbaoc_memprobe.so")
+
 _lib = None
+_probe = None
+
+
+def build_probe():
+    subprocess.run(["hipcc", *FLAGS, "-o", PROBE_LIB, PROBE_SRC], check=True, stderr=subprocess.DEVNULL)
+    return PROBE_LIB
+
+
+def probe_lib():
+    """The memory-system probe (csrc/memprobe.hip): pure streams with the step kernel's traffic mix."""
+    global _probe
+    if _probe is None:
+        if not os.path.exists(PROBE_LIB):
+            build_probe()
+        _probe = C.CDLL(PROBE_LIB)
+        _probe.synth_mem_probe.argtypes = [C.c_int, C.c_int, C.c_int, C.c_uint32, C.c_uint64,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    return _probe
 
 
 def build_lib():
