@@ -66,8 +66,7 @@ def cpu_baseline(w, ring, seed, params):
     import numpy as np
     from concurrent.futures import ThreadPoolExecutor
     import oracle
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import oracle_params, to_host_bits
+    from oracle.runner import oracle_params, to_host_bits
     budget = 250_000_000                                  # coordinates in the sample
     order = sorted(range(len(w.blocks)), key=lambda i: (abs(w.blocks[i].numel - 16_777_216), i))
     pick, tot = [], 0

@@ -93,9 +93,12 @@ def lib():
         L.orc_phi.restype = f64
         L.orc_phi.argtypes = [C.POINTER(Stats), C.c_char_p, C.c_int, C.POINTER(RiskParams)]
         for n in ("orc_allocate_brute", "orc_allocate_dp", "orc_allocate_bnb"):
-            if hasattr(L, n):
-                getattr(L, n).argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp,
-                                          C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
+            getattr(L, n).argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp,
+                                      C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)]
+        L.orc_allocate_bnb_set_node_limit.restype = None
+        L.orc_allocate_bnb_set_node_limit.argtypes = [u64]
+        L.orc_allocate_bnb_last_nodes.restype = u64
+        L.orc_allocate_bnb_last_nodes.argtypes = []
         L.orc_integerise.argtypes = [vp, vp, vp, u32, u32, i64, f64, vp, vp, vp, vp, C.POINTER(i64)]
         _lib = L
     return _lib
@@ -257,9 +260,16 @@ def allocate_dp(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
     return _allocate(lib().orc_allocate_dp, risk, mem, time, mem_budget, time_budget_sum, forbidden)
 
 
-def allocate_bnb(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):
-    """Depth-first branch and bound, for instances the other two cannot reach."""
+def allocate_bnb(risk, mem, time, mem_budget, time_budget_sum, forbidden=None, node_limit=0):
+    """Depth-first branch and bound in lexicographic order, for instances the other two cannot
+    reach.  node_limit: search nodes after which the call gives up with ORC_TOO_BIG (0 = default)."""
+    lib().orc_allocate_bnb_set_node_limit(int(node_limit))
     return _allocate(lib().orc_allocate_bnb, risk, mem, time, mem_budget, time_budget_sum, forbidden)
+
+
+def allocate_bnb_nodes():
+    """Search nodes of the last allocate_bnb call."""
+    return lib().orc_allocate_bnb_last_nodes()
 
 
 def integerise(risk, mem, time, mem_budget, time_budget_sum, forbidden=None):

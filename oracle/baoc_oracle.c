@@ -19,9 +19,12 @@
  * cases, exactly representable values under both quantisers, error bounds of
  * the quantisers, quantiles against a sort-based library routine, chi-square
  * anisotropy of isotropic noise, the normalisation constants of App. A,
- * Agg(c) of Eq. 1, and exhaustive enumeration / dynamic programming for the
- * allocation.  The end-to-end trajectory on a workload is parity unpinned
- * against the paper: it prints no statistic, risk or allocation.
+ * Agg(c) of Eq. 1, the order of NaN and +inf in the quantile against a library
+ * sort, the distance of the fp32 state sequence from the same definitions in
+ * fp64 throughout, and for the allocation exhaustive enumeration, a dense
+ * dynamic programme and a depth-first branch and bound checked against both.
+ * The end-to-end trajectory on a workload is parity unpinned against the
+ * paper: it prints no statistic, risk or allocation.
  */
 #include <math.h>
 #include <stdint.h>
@@ -604,4 +607,385 @@ int orc_integerise(const double *risk, const int64_t *mem, const double *time,
     }
     inst_free(&I);
     return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* Allocation (Eq. 2): depth-first branch and bound                     */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The third exact method, for instances that neither the enumeration nor the
+ * dynamic programme reaches.  Blocks are fixed in index order and, inside a
+ * block, configurations are tried in index order, so complete assignments are
+ * met in lexicographic order.  A complete assignment replaces the incumbent
+ * only when it is strictly better; the first optimum met is therefore the
+ * lexicographically smallest one and stays.
+ *
+ * Before the search, a configuration is struck from its block when another
+ * allowed one needs no more of either row and has less risk, or the same risk
+ * and a smaller index: exchanging it keeps an assignment feasible and makes it
+ * better or lexicographically smaller, so the answer never contains it.
+ *
+ * A partial assignment (a prefix) is abandoned when
+ *   - a row cannot be met any more (its use so far plus the least use of the
+ *     open blocks exceeds the budget), or
+ *   - weak duality shows that no completion reaches the cutoff: for any
+ *     multipliers l1, l2 >= 0 every feasible completion has
+ *       Z >= Z_fixed + l1 W_fixed + l2 T_fixed
+ *            + sum over open blocks of min_c (phi + l1 mem + l2 tau) - l1 B_mem - l2 B_tau.
+ *     The test is made in exact integers (multipliers are fractions L / S with
+ *     S a power of two) for a fixed ladder of multiplier pairs around the pair
+ *     that maximises the bound of the whole instance (found by alternating
+ *     bisections; any pair >= 0 is valid, a good one only saves time).
+ *     Pairs with S = 0 bound the rows alone: l1 W + l2 T of any completion
+ *     against l1 B_mem + l2 B_tau, which abandons prefixes that no completion
+ *     can bring inside both budgets at once; or
+ *   - a prefix of the same depth with Z_fixed, W_fixed and T_fixed all no
+ *     larger has been left before in this search: the open blocks are the
+ *     same, whatever completes this prefix within the budgets completed that
+ *     one too, with a total no larger; every such completion was abandoned or
+ *     met then, and the cutoff can only have fallen since.  Left states are
+ *     kept per depth (a list that is full simply stops growing).
+ *
+ * Cutoff.  All objective values lie on one lattice base + g Z (g = gcd of the
+ * differences of phi inside the blocks), so "strictly better" means "better by
+ * at least g": once a complete assignment of value z has been met, only totals
+ * <= z - g are of interest.  Until then totals <= `cut` are accepted, and
+ * cut = U works, U being the value of a feasible assignment (Lagrangian
+ * minimisers that happen to be feasible, improved by single exchanges; the sum
+ * of the largest risks when none is known).  On a coarse lattice (at most 64
+ * values between the bound of the whole instance and U) the search is instead
+ * run with the rising starting cutoffs low, low + g, ...: a search that meets
+ * nothing proves that the optimum lies above its starting cutoff, the first
+ * search that meets something returns the answer, and the searched window
+ * stays narrow even when U is poor.
+ *
+ * A node limit over all searches ends the call with ORC_TOO_BIG and no answer.
+ */
+typedef __int128 i128;
+
+static uint64_t bnb_node_limit = 2000000000ull;
+static uint64_t bnb_last_nodes = 0;
+
+void orc_allocate_bnb_set_node_limit(uint64_t n) { bnb_node_limit = n ? n : 2000000000ull; }
+uint64_t orc_allocate_bnb_last_nodes(void) { return bnb_last_nodes; }
+
+/* Minimiser of phi + l1 mem + l2 tau in every block (ties: less memory, then less time, then
+   the smaller index); returns its exact sums. */
+static void lagrangian_pick(const int_instance *I, double l1, double l2, uint32_t *pick,
+                            int64_t *Z, int64_t *W, int64_t *T)
+{
+    *Z = *W = *T = 0;
+    for (uint32_t i = 0; i < I->N; ++i) {
+        int have = 0; double best = 0.0; size_t bk = 0;
+        for (uint32_t c = 0; c < I->K; ++c) {
+            size_t k = (size_t)i * I->K + c;
+            if (!I->ok[k]) continue;
+            double v = (double)I->phi[k] + l1 * (double)I->mem[k] + l2 * (double)I->tau[k];
+            int better = !have || v < best ||
+                         (v == best && (I->mem[k] < I->mem[bk] || (I->mem[k] == I->mem[bk] && I->tau[k] < I->tau[bk])));
+            if (better) { have = 1; best = v; bk = k; }
+        }
+        pick[i] = (uint32_t)(bk - (size_t)i * I->K);
+        *Z += I->phi[bk]; *W += I->mem[bk]; *T += I->tau[bk];
+    }
+}
+
+typedef struct { const int_instance *I; uint32_t *pick, *best; int have; int64_t U; } bnb_start;
+
+/* Does the minimiser at (l1, l2) exceed row `row`?  A minimiser inside both budgets is a
+   feasible assignment: its value is an upper bound on the optimum. */
+static int row_exceeded(bnb_start *s, double l1, double l2, int row)
+{
+    int64_t Z, W, T;
+    lagrangian_pick(s->I, l1, l2, s->pick, &Z, &W, &T);
+    if (W <= s->I->B_mem && T <= s->I->B_tau && (!s->have || Z < s->U)) {
+        s->have = 1; s->U = Z; memcpy(s->best, s->pick, s->I->N * 4);
+    }
+    return row == 0 ? W > s->I->B_mem : T > s->I->B_tau;
+}
+
+/* Least multiplier of one row (the other fixed) at which the minimiser meets that row. */
+static double bisect_row(bnb_start *s, int row, double other)
+{
+    double lo = 0.0, hi = 1.0;
+    if (!(row == 0 ? row_exceeded(s, 0.0, other, 0) : row_exceeded(s, other, 0.0, 1))) return 0.0;
+    while ((row == 0 ? row_exceeded(s, hi, other, 0) : row_exceeded(s, other, hi, 1)) && hi < 1e18) hi *= 4.0;
+    if (hi >= 1e18) return 1e18;
+    for (int it = 0; it < 80; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (row == 0 ? row_exceeded(s, mid, other, 0) : row_exceeded(s, other, mid, 1)) lo = mid; else hi = mid;
+    }
+    return hi;
+}
+
+/* Lower the upper bound by single exchanges: while some block can move to another allowed
+   configuration with less risk and both rows still hold, take the exchange that gains most. */
+static void exchange_descent(bnb_start *s)
+{
+    const int_instance *I = s->I;
+    if (!s->have) return;
+    int64_t W = 0, T = 0;
+    for (uint32_t i = 0; i < I->N; ++i) { size_t k = (size_t)i * I->K + s->best[i]; W += I->mem[k]; T += I->tau[k]; }
+    for (;;) {
+        int64_t gain = 0; uint32_t bi = 0, bc = 0;
+        for (uint32_t i = 0; i < I->N; ++i) {
+            size_t cur = (size_t)i * I->K + s->best[i];
+            for (uint32_t c = 0; c < I->K; ++c) {
+                size_t k = (size_t)i * I->K + c;
+                if (!I->ok[k]) continue;
+                if (I->phi[cur] - I->phi[k] > gain && W - I->mem[cur] + I->mem[k] <= I->B_mem &&
+                    T - I->tau[cur] + I->tau[k] <= I->B_tau) { gain = I->phi[cur] - I->phi[k]; bi = i; bc = c; }
+            }
+        }
+        if (gain == 0) return;
+        size_t cur = (size_t)bi * I->K + s->best[bi], k = (size_t)bi * I->K + bc;
+        W += I->mem[k] - I->mem[cur]; T += I->tau[k] - I->tau[cur];
+        s->U -= gain; s->best[bi] = bc;
+    }
+}
+
+/* States (Z, W, T) of one depth whose subtree has been searched to the end; only those that no
+   other one undercuts in all three are kept. */
+typedef struct { int64_t *Z, *W, *T; uint32_t n, cap; } left_list;
+enum { LEFT_MAX = 4096 };                /* a list that is full simply stops growing */
+
+/* Has a state been left at this depth that had fixed no more risk and used no more of either row? */
+static int left_covers(const left_list *l, int64_t Z, int64_t W, int64_t T)
+{
+    for (uint32_t j = 0; j < l->n; ++j)
+        if (l->Z[j] <= Z && l->W[j] <= W && l->T[j] <= T) return 1;
+    return 0;
+}
+
+static void left_add(left_list *l, int64_t Z, int64_t W, int64_t T)
+{
+    uint32_t o = 0;
+    for (uint32_t j = 0; j < l->n; ++j)               /* drop what the new state makes redundant */
+        if (!(Z <= l->Z[j] && W <= l->W[j] && T <= l->T[j])) { l->Z[o] = l->Z[j]; l->W[o] = l->W[j]; l->T[o] = l->T[j]; ++o; }
+    l->n = o;
+    if (l->n >= LEFT_MAX) return;
+    if (l->n == l->cap) {
+        uint32_t cap = l->cap ? 2 * l->cap : 16;
+        int64_t *z = (int64_t *)realloc(l->Z, cap * 8), *w = (int64_t *)realloc(l->W, cap * 8), *t = (int64_t *)realloc(l->T, cap * 8);
+        if (z) l->Z = z;
+        if (w) l->W = w;
+        if (t) l->T = t;
+        if (!z || !w || !t) return;                   /* no room: the state is simply not recorded */
+        l->cap = cap;
+    }
+    l->Z[l->n] = Z; l->W[l->n] = W; l->T[l->n] = T; l->n += 1;
+}
+
+enum { BNB_MAXM = 26 + 7 };
+
+typedef struct {
+    const int_instance *I;
+    int64_t *sufW, *sufT;                /* least use of each row by the blocks i..N-1           */
+    int64_t g;                           /* lattice step of the objective                        */
+    int M;                               /* multiplier pairs                                     */
+    i128 S[BNB_MAXM], L1[BNB_MAXM], L2[BNB_MAXM], bud[BNB_MAXM];
+    i128 *rcst;                          /* [m][i*K+c]: S phi + L1 mem + L2 tau                  */
+    i128 *suf;                           /* [m][i]: sum over blocks >= i of the least rcst       */
+    i128 *pre;                           /* [m][depth]: sum of rcst over the fixed blocks        */
+    uint32_t *x, *best, *next;
+    int64_t *Zp, *Wp, *Tp;
+    left_list *left;                     /* [depth] */
+    uint64_t nodes;
+} bnb_ctx;
+
+/* One lexicographic depth-first search that accepts totals <= cut.  Returns 1 when a complete
+   assignment was met (c->best then holds the lexicographically smallest optimum), 0 when none
+   has a total <= cut, -1 when the node limit was reached. */
+static int bnb_search(bnb_ctx *c, int64_t cut)
+{
+    const int_instance *I = c->I;
+    const uint32_t N = I->N, K = I->K;
+    const size_t NK = (size_t)N * K, N1 = (size_t)N + 1;
+    int found = 0;
+    for (uint32_t d = 0; d <= N; ++d) c->left[d].n = 0;
+    int i = 0;
+    c->next[0] = 0; c->Zp[0] = c->Wp[0] = c->Tp[0] = 0;
+    for (int m = 0; m < c->M; ++m) c->pre[(size_t)m * N1] = 0;
+    while (i >= 0) {
+        if ((uint32_t)i == N) {                    /* complete, inside both rows, total <= cut */
+            found = 1; memcpy(c->best, c->x, N * 4);
+            cut = c->Zp[N] - c->g;
+            --i;
+            continue;
+        }
+        int went_down = 0;
+        for (uint32_t cfg = c->next[i]; cfg < K; ++cfg) {
+            size_t k = (size_t)i * K + cfg;
+            if (!I->ok[k]) continue;
+            if (++c->nodes > bnb_node_limit) return -1;
+            int64_t W = c->Wp[i] + I->mem[k], T = c->Tp[i] + I->tau[k];
+            if (W + c->sufW[i + 1] > I->B_mem || T + c->sufT[i + 1] > I->B_tau) continue;
+            int hopeless = 0;
+            for (int m = 0; m < c->M && !hopeless; ++m) {
+                i128 lhs = c->pre[(size_t)m * N1 + i] + c->rcst[(size_t)m * NK + k] + c->suf[(size_t)m * N1 + i + 1] - c->bud[m];
+                hopeless = lhs > c->S[m] * (i128)cut;
+            }
+            if (hopeless) continue;
+            if (left_covers(&c->left[i + 1], c->Zp[i] + I->phi[k], W, T)) continue;
+            c->x[i] = cfg; c->next[i] = cfg + 1;
+            c->Zp[i + 1] = c->Zp[i] + I->phi[k]; c->Wp[i + 1] = W; c->Tp[i + 1] = T;
+            for (int m = 0; m < c->M; ++m)
+                c->pre[(size_t)m * N1 + i + 1] = c->pre[(size_t)m * N1 + i] + c->rcst[(size_t)m * NK + k];
+            ++i; c->next[i] = 0;
+            went_down = 1;
+            break;
+        }
+        if (!went_down) {                          /* every completion of this prefix has been dealt with */
+            left_add(&c->left[i], c->Zp[i], c->Wp[i], c->Tp[i]);
+            --i;
+        }
+    }
+    return found;
+}
+
+static int64_t clamp_mult(double x) { return llround(x < 4e18 ? x : 4e18); }
+
+int orc_allocate_bnb(const double *risk, const int64_t *mem, const double *time,
+                     uint32_t N, uint32_t K, int64_t B_mem, double time_budget_sum,
+                     const uint8_t *forbidden, uint32_t *out_choice,
+                     double *out_obj, int64_t *out_mem, double *out_time)
+{
+    int_instance I;
+    int rc = integerise(risk, mem, time, N, K, B_mem, time_budget_sum, forbidden, &I);
+    if (rc) { inst_free(&I); return rc; }
+    bnb_last_nodes = 0;
+    const size_t NK = (size_t)N * K, N1 = (size_t)N + 1;
+
+    /* strike configurations that another one of the same block makes pointless (see above) */
+    for (uint32_t b = 0; b < N; ++b)
+        for (uint32_t c = 0; c < K; ++c) {
+            size_t k = (size_t)b * K + c;
+            if (!I.ok[k]) continue;
+            for (uint32_t e = 0; e < K; ++e) {
+                size_t q = (size_t)b * K + e;
+                if (e == c || !I.ok[q]) continue;   /* a struck one (ok == 2) still shows that k is pointless */
+                if (I.mem[q] <= I.mem[k] && I.tau[q] <= I.tau[k] &&
+                    (I.phi[q] < I.phi[k] || (I.phi[q] == I.phi[k] && e < c))) { I.ok[k] = 2; break; }
+            }
+        }
+    for (size_t k = 0; k < NK; ++k)
+        if (I.ok[k] == 2) I.ok[k] = 0;
+
+    bnb_ctx C;
+    memset(&C, 0, sizeof(C));
+    C.I = &I;
+    C.sufW = (int64_t *)calloc(N1, 8); C.sufT = (int64_t *)calloc(N1, 8);
+    int64_t zmax = 0;
+    int dead_block = 0;
+    double sum_mem = 0.0, spreadW = 1.0, spreadT = 1.0;
+    for (int i = (int)N - 1; i >= 0; --i) {
+        int have = 0; int64_t lw = 0, hw = 0, lt = 0, ht = 0, first_phi = 0, hphi = 0;
+        for (uint32_t c = 0; c < K; ++c) {
+            size_t k = (size_t)i * K + c;
+            if (!I.ok[k]) continue;
+            if (!have) { have = 1; lw = hw = I.mem[k]; lt = ht = I.tau[k]; first_phi = hphi = I.phi[k]; }
+            if (I.mem[k] < lw) lw = I.mem[k];
+            if (I.mem[k] > hw) hw = I.mem[k];
+            if (I.tau[k] < lt) lt = I.tau[k];
+            if (I.tau[k] > ht) ht = I.tau[k];
+            if (I.phi[k] > hphi) hphi = I.phi[k];
+            C.g = gcd64(C.g, I.phi[k] - first_phi);
+        }
+        if (!have) dead_block = 1;
+        C.sufW[i] = C.sufW[i + 1] + lw; C.sufT[i] = C.sufT[i + 1] + lt;
+        zmax += hphi; sum_mem += (double)hw;
+        spreadW += (double)(hw - lw); spreadT += (double)(ht - lt);
+    }
+    if (C.g == 0) C.g = 1;
+    if (sum_mem > 4e18) rc = ORC_TOO_BIG;
+    else if (dead_block || C.sufW[0] > I.B_mem || C.sufT[0] > I.B_tau) rc = ORC_INFEASIBLE;
+    if (rc) { free(C.sufW); free(C.sufT); inst_free(&I); return rc; }
+
+    /* multipliers of the whole instance, and an upper bound from the minimisers seen on the way */
+    bnb_start st; st.I = &I; st.pick = (uint32_t *)calloc(N, 4); st.best = (uint32_t *)calloc(N, 4); st.have = 0; st.U = 0;
+    double l1 = 0.0, l2 = 0.0;
+    for (int round = 0; round < 3; ++round) {
+        l1 = bisect_row(&st, 0, l2);
+        l2 = bisect_row(&st, 1, l1);
+    }
+    exchange_descent(&st);
+    const int64_t U = st.have ? st.U : zmax;      /* some assignment inside both rows has a total <= U */
+
+    /* ladder of multiplier pairs as exact fractions L / S; pair 0 is (l1, l2) itself */
+    static const double step[5] = {1.0, 0.5, 2.0, 0.25, 4.0};
+    for (int a = 0; a < 5; ++a)
+        for (int b = 0; b < 5; ++b) {
+            if ((a > 0 && l1 == 0.0) || (b > 0 && l2 == 0.0)) continue;
+            double m1 = l1 * step[a], m2 = l2 * step[b];
+            double mx = m1 > m2 ? m1 : m2;
+            int k = 40;
+            while (k > 0 && ldexp(mx, k) > 4e18) --k;
+            C.S[C.M] = (i128)1 << k;
+            C.L1[C.M] = (i128)clamp_mult(ldexp(m1, k));
+            C.L2[C.M] = (i128)clamp_mult(ldexp(m2, k));
+            ++C.M;
+        }
+    C.S[C.M] = 1; C.L1[C.M] = 0; C.L2[C.M] = 0; ++C.M;          /* (0,0): the plain objective bound */
+    {   /* the rows alone (S = 0): weights theta / spread of the memory row, (1 - theta) / spread of the time row */
+        static const double theta[7] = {0.5, 0.25, 0.75, 0.1, 0.9, 0.02, 0.98};
+        for (int a = 0; a < 7; ++a) {
+            C.S[C.M] = 0;
+            C.L1[C.M] = (i128)clamp_mult(ldexp(theta[a] / spreadW, 62));
+            C.L2[C.M] = (i128)clamp_mult(ldexp((1.0 - theta[a]) / spreadT, 62));
+            ++C.M;
+        }
+    }
+
+    /* reduced costs, their least value per block summed over the open blocks, the budget terms */
+    C.rcst = (i128 *)malloc((size_t)C.M * NK * sizeof(i128));
+    C.suf = (i128 *)malloc((size_t)C.M * N1 * sizeof(i128));
+    C.pre = (i128 *)malloc((size_t)C.M * N1 * sizeof(i128));
+    for (int m = 0; m < C.M; ++m) {
+        C.bud[m] = C.L1[m] * (i128)I.B_mem + C.L2[m] * (i128)I.B_tau;
+        C.suf[(size_t)m * N1 + N] = 0;
+        for (int i = (int)N - 1; i >= 0; --i) {
+            int have = 0; i128 least = 0;
+            for (uint32_t c = 0; c < K; ++c) {
+                size_t k = (size_t)i * K + c;
+                i128 v = C.S[m] * (i128)I.phi[k] + C.L1[m] * (i128)I.mem[k] + C.L2[m] * (i128)I.tau[k];
+                C.rcst[(size_t)m * NK + k] = v;
+                if (!I.ok[k]) continue;
+                if (!have || v < least) { have = 1; least = v; }
+            }
+            C.suf[(size_t)m * N1 + i] = C.suf[(size_t)m * N1 + i + 1] + least;
+        }
+    }
+    C.x = (uint32_t *)calloc(N, 4); C.best = (uint32_t *)calloc(N, 4); C.next = (uint32_t *)calloc(N1, 4);
+    C.Zp = (int64_t *)calloc(N1, 8); C.Wp = (int64_t *)calloc(N1, 8); C.Tp = (int64_t *)calloc(N1, 8);
+    C.left = (left_list *)calloc(N1, sizeof(left_list));
+
+    /* Smallest lattice value the bound of the whole instance allows: the optimum Z* satisfies
+       S Z* >= suf[0][0] - bud[0], and Z* = U - j g for some j >= 0. */
+    int64_t low = U;
+    {
+        i128 lb = C.suf[0] - C.bud[0];                         /* scaled by S[0] */
+        i128 room = (i128)U * C.S[0] - lb;                     /* S (U - LB) */
+        if (room > 0) {
+            i128 j = room / (C.S[0] * (i128)C.g);              /* floor((U - LB) / g) */
+            low = U - (int64_t)j * C.g;
+        }
+    }
+    /* rising starting cutoffs low, low + g, ... up to U while only a few lattice values lie between
+       (a coarse lattice: ties are everywhere and a poor U costs most); otherwise U at once */
+    int found = 0;
+    int64_t cut = (U - low) / C.g <= 64 ? low : U;
+    for (;;) {
+        found = bnb_search(&C, cut);
+        if (found || cut >= U) break;
+        cut += C.g;
+    }
+    bnb_last_nodes = C.nodes;
+    if (found == 1) { memcpy(out_choice, C.best, N * 4); report(&I, C.best, out_obj, out_mem, out_time); }
+    free(C.x); free(C.best); free(C.next); free(C.Zp); free(C.Wp); free(C.Tp);
+    for (uint32_t d = 0; d <= N; ++d) { free(C.left[d].Z); free(C.left[d].W); free(C.left[d].T); }
+    free(C.left);
+    free(C.rcst); free(C.suf); free(C.pre); free(st.pick); free(st.best); free(C.sufW); free(C.sufT); inst_free(&I);
+    if (found < 0) return ORC_TOO_BIG;
+    return found ? ORC_OK : ORC_INFEASIBLE;
 }

@@ -1,4 +1,8 @@
-"""Shared by the GPU parity tests: run both sides on the same device-generated stream and compare."""
+"""Running the oracle next to a device stream and comparing results with it.
+
+TEST INFRASTRUCTURE ONLY, like the rest of this package: used by the tests, by the smoke check and by the
+benchmark's cpu_baseline leg.  Holds no arithmetic of the method: it copies device buffers to the host, feeds
+them to oracle.Block and states the tolerance of the comparison."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np

@@ -239,6 +239,26 @@ def make(name: str, pad: int = 64, seed: int = 1) -> Workload:
     return w
 
 
+def ragged(dtype, pad, reverse=False):
+    """Correctness layout: block sizes around the 64 / 256 / 1024 boundaries, 1- and 3-coordinate blocks,
+    thin and ragged matrix shapes, optionally packed tightly (pad = 1: arbitrary offsets) or listed in
+    reverse order.  K = 6 candidates, stream parameters of seed 5."""
+    sizes = [1, 3, 63, 64, 255, 256, 257, 1000, 4099, 9408, 70001, 5, 1024 * 33 + 7]
+    shapes = {3: (8, 8), 4: (5, 51), 5: (256, 1), 7: (10, 100), 8: (4099, 1), 9: (64, 147), 10: (70001, 1), 12: (73, 463)}
+    blocks = []
+    for i, n in enumerate(sizes):
+        r, c = shapes.get(i, (0, 0))
+        if r * c != n:
+            r, c = (0, 0)
+        blocks.append(BlockSpec(f"r{i}", n, r, c))
+    blocks.append(_mat("wide", 3, 1027)); blocks.append(_mat("tall", 1030, 3)); blocks.append(_mat("sq", 300, 260))
+    w = Workload("ragged", blocks, 5, dtype, "cycle", **K6)
+    layout(w, pad); draw_stream_params(w, 5)
+    if reverse:
+        w.blocks.reverse()
+    return w
+
+
 WORKLOADS = ["tiny", "resnet50", "gpt2_small", "unet", "gpt_1p3b", "llama7b"]
 
 

@@ -42,7 +42,7 @@ def test_blocks_beyond_2_to_the_31_coordinates(env):  # noqa: F811
     intensive statistics equal those of a small oracle block on the same gradient and the extensive ones scale
     with d exactly (no coordinate skipped or counted twice where 32-bit indices would wrap)."""
     import oracle
-    from helpers import oracle_params
+    from oracle.runner import oracle_params
     torch, binding = env["torch"], env["binding"]
     d_vec = (1 << 31) + (1 << 29) + 12_345
     rows, cols = 40_000, 60_001                                   # 2,400,040,000 > 2^31, cols not a multiple of 4

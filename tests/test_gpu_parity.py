@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import (OracleRunner, assert_risk_close, assert_stats_close, oracle_params, to_host_bits)
+from oracle.runner import (OracleRunner, assert_risk_close, assert_stats_close, oracle_params, to_host_bits)
 from synth import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -70,21 +70,7 @@ def test_tiny_bf16_gradients(env):
     run_both(env, w, 6, theta_dtype=env["torch"].bfloat16)
 
 
-def ragged_workload(dtype, pad, reverse=False):
-    sizes = [1, 3, 63, 64, 255, 256, 257, 1000, 4099, 9408, 70001, 5, 1024 * 33 + 7]
-    shapes = {3: (8, 8), 4: (5, 51), 5: (256, 1), 7: (10, 100), 8: (4099, 1), 9: (64, 147), 10: (70001, 1), 12: (73, 463)}
-    blocks = []
-    for i, n in enumerate(sizes):
-        r, c = shapes.get(i, (0, 0))
-        if r * c != n:
-            r, c = (0, 0)
-        blocks.append(W.BlockSpec(f"r{i}", n, r, c))
-    blocks.append(W._mat("wide", 3, 1027)); blocks.append(W._mat("tall", 1030, 3)); blocks.append(W._mat("sq", 300, 260))
-    w = W.Workload("ragged", blocks, 5, dtype, "cycle", **W.K6)
-    W.layout(w, pad); W.draw_stream_params(w, 5)
-    if reverse:
-        w.blocks.reverse()
-    return w
+ragged_workload = W.ragged
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import assert_stats_close, oracle_params, to_host_bits
+from oracle.runner import assert_stats_close, oracle_params, to_host_bits
 from synth import workloads as W
 from test_gpu_parity import env, ragged_workload  # noqa: F401
 

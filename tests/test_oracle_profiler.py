@@ -333,3 +333,110 @@ def test_blocks_are_independent():
     for f in other:
         q.step(f)
     assert p.state[1].finalize().asdict() == q.state[1].finalize().asdict()
+
+
+# ---------------------------------------------------------------- non-finite second moments in the quantile (Eq. 4)
+
+def test_quantile_ranks_nan_above_infinity_like_a_library_sort():
+    """numpy.sort places NaN after +inf; the order statistics the oracle interpolates between must be the
+    same ones, whatever mixture of finite values, +inf and NaN the block holds."""
+    def library(x, q):
+        s = np.sort(x.astype(np.float64))
+        pos = q * (s.size - 1); lo = int(math.floor(pos)); hi = min(lo + 1, s.size - 1)
+        with np.errstate(invalid="ignore"):
+            return s[lo] + (pos - lo) * (s[hi] - s[lo])
+    for trial in range(40):
+        d = int(RNG.integers(5, 400))
+        x = (RNG.standard_normal(d) ** 2).astype(np.float32)
+        n_inf, n_nan = int(RNG.integers(0, max(1, d // 4))), int(RNG.integers(0, max(1, d // 4)))
+        where = RNG.permutation(d)
+        x[where[:n_inf]] = np.inf
+        x[where[n_inf:n_inf + n_nan]] = np.nan
+        for q in (0.0, 0.1, 0.5, 0.9, 1.0, float(RNG.random())):
+            got, want = oracle.quantile(x, q), library(x, q)
+            assert (np.isnan(got) and np.isnan(want)) or got == want, (trial, d, n_inf, n_nan, q, got, want)
+    # the cases spelled out: NaN is the largest, +inf the next (an infinite or NaN neighbour turns the
+    # interpolated value into NaN even at weight 0, as IEEE arithmetic has it: 0 * inf)
+    x = np.array([3.0, np.nan, 1.0, np.inf, 2.0], np.float32)          # ascending: 1 2 3 inf nan
+    assert oracle.quantile(x, 0.0) == 1.0 and oracle.quantile(x, 0.25) == 2.0 and oracle.quantile(x, 0.375) == 2.5
+    assert np.isnan(oracle.quantile(x, 0.5)) and np.isnan(oracle.quantile(x, 1.0))
+    assert oracle.quantile(np.array([np.nan, 5.0, 7.0], np.float32), 0.0) == 5.0
+    assert oracle.quantile(np.array([np.inf, np.nan, 5.0, 7.0, 6.0], np.float32), 0.25) == 6.0
+
+
+# ---------------------------------------------------------------- the fixed fp32 state sequence against the plain fp64 definitions
+
+def _round_to_significand(x, bits):
+    m, e = np.frexp(x)
+    return np.ldexp(np.rint(m * 2.0 ** bits) / 2.0 ** bits, e)         # nearest, ties to even, no exponent limits
+
+
+def _definitions_in_fp64(gs, qb=256, eps=1e-12):
+    """Eq. 3, Eq. 4, Eq. 5 (right) and Eq. 8 evaluated in fp64 throughout: states advanced as
+    beta x + (1 - beta) y, 8-bit codes decided as rint(L x / a) in fp64, bf16 as the nearest 8-bit significand."""
+    eu = float(np.float32(1e-8))
+    d = gs[0].size
+    m, v = np.zeros(d), np.zeros(d)
+    for g in gs:
+        g = g.astype(np.float64)
+        m = BM * m + (1 - BM) * g
+        v = BV * v + (1 - BV) * g * g
+    out = {}
+    S_mm, S_v1, S_vv = float((m * m).sum()), float(v.sum()), float((v * v).sum())
+    out["m_sq"], out["v_l1"], out["snr"] = S_mm, S_v1, S_mm / (S_v1 + eps)
+    out["q10"], out["q90"] = (float(np.quantile(v, q)) for q in (0.1, 0.9))
+    out["A"] = math.log((out["q90"] + eps) / (out["q10"] + eps))
+    code_m, code_v = np.zeros(d), np.zeros(d)
+    m8, v8 = np.zeros(d), np.zeros(d)
+    for s in range(0, d, qb):
+        sl = slice(s, min(d, s + qb))
+        am, av = np.abs(m[sl]).max(), v[sl].max()
+        if am > 0:
+            code_m[sl] = np.rint(127 * m[sl] / am); m8[sl] = am * code_m[sl] / 127
+        if av > 0:
+            code_v[sl] = np.rint(255 * v[sl] / av); v8[sl] = av * code_v[sl] / 255
+    m16, v16 = _round_to_significand(m, 8), _round_to_significand(v, 8)
+    u32 = m / (np.sqrt(v) + eu)
+    for tag, mq, vq in (("16", m16, v16), ("8", m8, v8)):
+        ub = mq / (np.sqrt(vq) + eu)
+        q = float((u32 * ub).sum() / (math.sqrt((u32 * u32).sum()) * math.sqrt((ub * ub).sum()) + eps))
+        out["Q" + tag] = min(max(q, eps), 1.0)
+        out["lQ" + tag] = -math.log(out["Q" + tag] + eps)
+        out["err_m" + tag] = math.sqrt(((mq - m) ** 2).sum()) / (math.sqrt(S_mm) + eps)
+        out["err_v" + tag] = math.sqrt(((vq - v) ** 2).sum()) / (math.sqrt(S_vv) + eps)
+    return out, code_m, code_v, m16, v16
+
+
+def test_fp32_state_sequence_stays_close_to_the_fp64_definitions():
+    """The oracle advances m, v in one fixed fp32 sequence and decides the 8-bit codes in fp32 (so that the
+    kernels can be compared bit for bit).  Measured against the same definitions in fp64 throughout, on the
+    ragged layout's stream: every reported statistic moves by less than a fifth of the parity tolerance
+    (largest seen: 9e-6 relative, the bf16 error of v on a 4,099-coordinate block), including the blocks
+    where a quantiser decision flips between the two evaluations."""
+    from synth import gradgen, workloads as W
+    w = W.ragged("f32", 1)
+    flipped, worst = [], 0.0
+    for i, b in enumerate(w.blocks):
+        gs = [gradgen.block_gradient(5, i, b, t) for t in range(1, w.T + 1)]
+        ob = run(gs)
+        st = ob.finalize()
+        ref, code_m, code_v, m16, v16 = _definitions_in_fp64(gs)
+        om, ov = ob.m, ob.v
+        flips = 0
+        for s in range(0, b.numel, 256):
+            sl = slice(s, min(b.numel, s + 256))
+            am, av = float(np.abs(om[sl]).max()), float(ov[sl].max())
+            flips += sum(oracle.q8_code(x, am, 127.0) != k for x, k in zip(om[sl], code_m[sl]))
+            flips += sum(oracle.q8_code(x, av, 255.0) != k for x, k in zip(ov[sl], code_v[sl]))
+        flips += int((m16 != np.array([oracle.bf16_round(x) for x in om])).sum())
+        flips += int((v16 != np.array([oracle.bf16_round(x) for x in ov])).sum())
+        if flips:
+            flipped.append((b.name, b.numel, flips))
+        for k, r in ref.items():
+            shift = abs(getattr(st, k) - r) / (1e-6 + 1e-4 * abs(r))      # 1.0 = the parity tolerance
+            worst = max(worst, shift)
+            assert shift < 0.2, (b.name, b.numel, k, getattr(st, k), r)
+    # decisions do flip now and then (a value within an fp32 rounding of a code boundary); they are rare and,
+    # by the assertion above, invisible in the statistics even on the 1-, 3- and 5-coordinate blocks
+    assert len(flipped) <= 4 and all(n >= 1000 and f <= max(3, n // 5000) for _, n, f in flipped), flipped
+    assert 0.0 < worst < 0.2

@@ -201,3 +201,67 @@ def test_integer_image():
     rc, phi, tau, ok, bt = oracle.integerise(risk, mem, time, 10, 2.5)
     assert rc == 0 and list(phi[0][:3]) == [123456789, 10 ** 15, -10 ** 15] and list(ok[0]) == [1, 1, 1, 0]
     assert list(tau[0][:2]) == [1250000, 0] and bt == 2500000
+
+
+# ---------------------------------------------------------------- depth-first branch and bound
+
+def _same(a, b):
+    assert a[0] == b[0], (a[0], b[0])
+    if a[0] == 0:
+        assert list(a[1]) == list(b[1]) and a[2:] == b[2:]
+
+
+@pytest.mark.parametrize("kind", ["real", "int", "flat"])
+def test_branch_and_bound_agrees_with_enumeration(kind):
+    for trial in range(80):
+        N, K = int(RNG.integers(1, 9)), int(RNG.integers(1, 5))
+        risk, mem, time, bm, bt = random_instance(N, K, int_risk=(kind == "int"))
+        if kind == "flat":
+            risk = np.zeros((N, K))
+        fb = (RNG.random((N, K)) < 0.15).astype(np.uint8) if trial % 3 == 0 else None
+        if trial % 7 == 0:
+            risk = risk.copy(); risk[RNG.integers(0, N), RNG.integers(0, K)] = np.nan      # an excluded pair
+        _same(oracle.allocate_brute(risk, mem, time, bm, bt, fb), oracle.allocate_bnb(risk, mem, time, bm, bt, fb))
+
+
+@pytest.mark.parametrize("kind", ["real", "int", "flat"])
+def test_branch_and_bound_agrees_with_dynamic_programme(kind):
+    for trial in range(15):
+        N, K = int(RNG.integers(20, 60)), int(RNG.integers(3, 8))
+        risk, mem, time, bm, bt = random_instance(N, K, int_risk=(kind == "int"), mem_hi=12, tau_units=5)
+        if kind == "flat":
+            risk = np.zeros((N, K))
+        _same(oracle.allocate_dp(risk, mem, time, bm, bt), oracle.allocate_bnb(risk, mem, time, bm, bt))
+
+
+def test_branch_and_bound_special_cases():
+    risk = np.array([[0.1, 0.8], [0.3, 0.5]]); mem = np.array([[4, 1], [4, 1]], np.int64); time = np.ones((2, 2))
+    rc, x, obj, m, t = oracle.allocate_bnb(risk, mem, time, 5, 10.0)
+    assert rc == 0 and list(x) == [0, 1] and obj == pytest.approx(0.6) and m == 5 and t == 2.0
+    assert oracle.allocate_bnb(risk, mem, time, 1, 10.0)[0] == oracle.ORC_INFEASIBLE
+    assert oracle.allocate_bnb(risk, mem, time, 8, 1.5)[0] == oracle.ORC_INFEASIBLE
+    rc, x, *_ = oracle.allocate_bnb(risk, mem, time, 8, 10.0, forbidden=np.array([[1, 0], [0, 0]]))
+    assert rc == 0 and list(x) == [1, 0]
+    # ties: all assignments with total memory <= 3 cost 0; the smallest vector is (0, 1, 2)
+    rc, x, *_ = oracle.allocate_bnb(np.zeros((3, 3)), np.array([[2, 1, 0]] * 3, np.int64), np.ones((3, 3)), 3, 1e6)
+    assert rc == 0 and list(x) == [0, 1, 2]
+    # slack budgets: per-block arg-min, lowest index on ties
+    r = RNG.integers(0, 3, (40, 5)).astype(np.float64)
+    rc, x, *_ = oracle.allocate_bnb(r, RNG.integers(0, 9, (40, 5)), np.round(RNG.random((40, 5)) * 4) / 4, 10 ** 9, 1e6)
+    assert rc == 0 and list(x) == list(np.argmin(r, axis=1))
+    # rows that no assignment meets together although each can be met alone: proved, not guessed
+    mem = np.array([[0, 9]] * 6, np.int64); time = np.array([[9.0, 0.0]] * 6)
+    assert oracle.allocate_bnb(np.zeros((6, 2)), mem, time, 26, 26.0)[0] == oracle.ORC_INFEASIBLE
+    assert oracle.allocate_brute(np.zeros((6, 2)), mem, time, 26, 26.0)[0] == oracle.ORC_INFEASIBLE
+    assert oracle.allocate_bnb(np.zeros((6, 2)), mem, time, 27, 27.0)[0] == 0
+
+
+def test_branch_and_bound_gives_up_rather_than_guess():
+    risk, mem, time, _, _ = random_instance(40, 6)
+    bm = int(mem.min(1).sum() + 0.5 * (mem.max(1).sum() - mem.min(1).sum()))
+    bt = float(time.min(1).sum() + 0.5 * (time.max(1).sum() - time.min(1).sum()))
+    rc, *_ = oracle.allocate_bnb(risk, mem, time, bm, bt, node_limit=5)
+    assert rc == oracle.ORC_TOO_BIG
+    a = oracle.allocate_bnb(risk, mem, time, bm, bt)
+    assert a[0] == 0 and oracle.allocate_bnb_nodes() > 5
+    _same(oracle.allocate_dp(risk, mem, time, bm, bt), a)
