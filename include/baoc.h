@@ -147,6 +147,21 @@ int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
                        const baoc_profile_params* params,
                        void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out);
 
+/* baoc_profile_begin for callers that cannot allocate device memory (code between the begin and the
+ * end of a HIP graph capture, serving loops, harnesses that forbid hipMalloc): the workspace is an
+ * array of BAOC_STATIC_WORKSPACE_BYTES that the library holds on every GPU it is loaded on, from load
+ * until the process ends.  The call, and the step / finalize / end calls on its handle, allocate no
+ * device memory.  Everything else is as in baoc_profile_begin: the same kernels, bit-identical results.
+ * The array keeps what the last handle left in it (begin clears what must start at zero), and all
+ * handles begun this way on one GPU share it: only one may be alive per GPU at a time (a second begin
+ * before baoc_profile_end returns STATE), and work still queued on a stream for an ended handle races
+ * with the next one.  Errors: WORKSPACE when baoc_profile_workspace_bytes of the layout exceeds
+ * BAOC_STATIC_WORKSPACE_BYTES (about 13 M coordinates with bf16 gradients, 11 M with fp32);
+ * UNSUPPORTED for a device ordinal above 63; otherwise as baoc_profile_begin. */
+#define BAOC_STATIC_WORKSPACE_BYTES (128ull << 20)
+int baoc_profile_begin_static(const baoc_block* blocks, uint32_t n_blocks,
+                              const baoc_profile_params* params, baoc_profiler** out);
+
 /* One sampled step (Eq. 3, Eq. 5, Eq. 8): enqueue, on `hip_stream`
  * (a hipStream_t, NULL = null stream), one fused pass over the flat gradient
  * buffer `d_grad_flat` (DEVICE, grad_numel elements of the dtype given at

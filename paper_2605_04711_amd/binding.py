@@ -14,6 +14,7 @@ from . import build as _build
 
 OK, ERR_INVALID, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP, ERR_INFEASIBLE, ERR_LIMIT, ERR_STATE = 0, -1, -2, -3, -4, -5, -6, -7
 GRAD_F32, GRAD_BF16 = 0, 1
+STATIC_WORKSPACE_BYTES = 128 << 20      # BAOC_STATIC_WORKSPACE_BYTES
 
 
 class Block(C.Structure):
@@ -78,6 +79,7 @@ def load_library():
     L.baoc_risk_params_default.restype = None
     L.baoc_profile_workspace_bytes.argtypes = [C.POINTER(Block), u32, C.POINTER(ProfileParams), C.POINTER(u64)]
     L.baoc_profile_begin.argtypes = [C.POINTER(Block), u32, C.POINTER(ProfileParams), vp, u64, C.POINTER(vp)]
+    L.baoc_profile_begin_static.argtypes = [C.POINTER(Block), u32, C.POINTER(ProfileParams), C.POINTER(vp)]
     L.baoc_profile_step.argtypes = [vp, vp, u64, vp]
     L.baoc_profile_finalize.argtypes = [vp, C.POINTER(Config), u32, C.POINTER(RiskParams),
                                         C.POINTER(BlockStats), vp, vp]
@@ -156,7 +158,9 @@ class Profiler:
 
     blocks: sequence of (offset, numel[, rows, cols]) or objects with those attributes.
     workspace: optional caller-owned uint8 device tensor of at least workspace_bytes(blocks, params)
-    bytes, 256-byte aligned; its previous contents do not matter.
+    bytes, 256-byte aligned; its previous contents do not matter.  workspace="static" uses the
+    library's own per-GPU array instead (baoc_profile_begin_static: no device allocation at all,
+    layouts up to STATIC_WORKSPACE_BYTES, one such profiler alive per GPU).
     """
 
     def __init__(self, blocks, params=None, device="cuda:0", workspace=None, **kw):
@@ -170,12 +174,20 @@ class Profiler:
         _check(self.lib.baoc_profile_workspace_bytes(self._blocks, self.n_blocks, C.byref(self.params), C.byref(nbytes)),
                "baoc_profile_workspace_bytes")
         self.device = torch.device(device)
+        self._h = C.c_void_p()
+        if isinstance(workspace, str):
+            if workspace != "static":
+                raise ValueError('workspace must be a tensor, None or "static"')
+            self.workspace = None
+            with torch.cuda.device(self.device):
+                _check(self.lib.baoc_profile_begin_static(self._blocks, self.n_blocks, C.byref(self.params), C.byref(self._h)),
+                       "baoc_profile_begin_static")
+            return
         if workspace is None:
             workspace = torch.empty(nbytes.value, dtype=torch.uint8, device=self.device)
         elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != self.device:
             raise TypeError(f"workspace must be a contiguous uint8 tensor on {self.device}")
         self.workspace = workspace
-        self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(self.lib.baoc_profile_begin(self._blocks, self.n_blocks, C.byref(self.params),
                                                self.workspace.data_ptr(), self.workspace.numel(), C.byref(self._h)),
@@ -232,6 +244,8 @@ class Profiler:
         torch = self._torch
         pm, pv, pg = C.c_void_p(), C.c_void_p(), C.c_void_p()
         _check(self.lib.baoc_profile_state(self._h, block, C.byref(pm), C.byref(pv), C.byref(pg)), "baoc_profile_state")
+        if self.workspace is None:
+            raise RuntimeError("state views need a torch-owned workspace")
         base = self.workspace.data_ptr()
         n = self._blocks[block].numel
         gsz = 4 if self.params.grad_dtype == GRAD_F32 else 2

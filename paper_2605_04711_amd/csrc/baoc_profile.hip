@@ -1048,6 +1048,15 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
 
 using namespace baoc;
 
+// Workspace of baoc_profile_begin_static: one array per GPU, resident from the moment the code object is
+// loaded until the process ends.  In host code the name below is only a handle for hipGetSymbolAddress;
+// the device address is looked up once per device and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[BAOC_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each GPU
+static bool g_scratch_busy[kMaxDevices] = {};      // a handle begun with baoc_profile_begin_static is alive
+
 struct Plan {
     uint64_t n_chunks = 0;
     uint32_t gpw = 1, nw = 4, slices = 1, slice_groups = 4, resident = 8;   // launch shape of the step kernel
@@ -1069,6 +1078,7 @@ struct baoc_profiler {
     Plan plan;
     std::vector<baoc_block> blocks;
     char* ws = nullptr;
+    int static_device = -1;       // >= 0: the workspace is that device's `scratch` array
     uint32_t steps = 0;
     uint64_t max_end = 0;         // largest offset + numel over the blocks
     int sticky = BAOC_OK;
@@ -1248,11 +1258,10 @@ extern "C" int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n
     return BAOC_OK;
 }
 
-extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
-                                  const baoc_profile_params* params,
-                                  void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out)
+// Shared by the two begin calls: plan, carve `d_workspace`, clear what must start at zero, upload the tables.
+static int begin_on(const baoc_block* blocks, uint32_t n_blocks, const baoc_profile_params* params,
+                    void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out)
 {
-    if (!out || !d_workspace) return BAOC_ERR_INVALID;
     baoc_profiler* h = new (std::nothrow) baoc_profiler();
     if (!h) return BAOC_ERR_INVALID;
     int rc = make_plan(blocks, n_blocks, params, &h->plan, &h->max_end);
@@ -1283,6 +1292,32 @@ extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
     h->h_ostat.resize((size_t)n_blocks * 4);
     *out = h;
     return BAOC_OK;
+}
+
+extern "C" int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
+                                  const baoc_profile_params* params,
+                                  void* d_workspace, uint64_t workspace_bytes, baoc_profiler** out)
+{
+    if (!out || !d_workspace) return BAOC_ERR_INVALID;
+    return begin_on(blocks, n_blocks, params, d_workspace, workspace_bytes, out);
+}
+
+extern "C" int baoc_profile_begin_static(const baoc_block* blocks, uint32_t n_blocks,
+                                         const baoc_profile_params* params, baoc_profiler** out)
+{
+    if (!out) return BAOC_ERR_INVALID;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return BAOC_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDevices) return BAOC_ERR_UNSUPPORTED;
+    if (g_scratch_busy[dev]) return BAOC_ERR_STATE;            // one handle at a time shares the array
+    if (!g_scratch_ptr[dev]) {                                 // first use on this device: where its copy of the array lives
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return BAOC_ERR_HIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    const int rc = begin_on(blocks, n_blocks, params, g_scratch_ptr[dev], BAOC_STATIC_WORKSPACE_BYTES, out);
+    if (rc == BAOC_OK) { (*out)->static_device = dev; g_scratch_busy[dev] = true; }
+    return rc;
 }
 
 extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint64_t grad_numel, void* hip_stream)
@@ -1460,6 +1495,7 @@ extern "C" int baoc_profile_state(const baoc_profiler* h, uint32_t block,
 extern "C" int baoc_profile_end(baoc_profiler* h)
 {
     if (!h) return BAOC_ERR_INVALID;
+    if (h->static_device >= 0) g_scratch_busy[h->static_device] = false;
     delete h;
     return BAOC_OK;
 }
