@@ -748,7 +748,7 @@ static void exchange_descent(bnb_start *s)
 /* States (Z, W, T) of one depth whose subtree has been searched to the end; only those that no
    other one undercuts in all three are kept. */
 typedef struct { int64_t *Z, *W, *T; uint32_t n, cap; } left_list;
-enum { LEFT_MAX = 4096 };                /* a list that is full simply stops growing */
+enum { LEFT_MAX = 1024 };                /* a list that is full simply stops growing */
 
 /* Has a state been left at this depth that had fixed no more risk and used no more of either row? */
 static int left_covers(const left_list *l, int64_t Z, int64_t W, int64_t T)
@@ -912,8 +912,8 @@ int orc_allocate_bnb(const double *risk, const int64_t *mem, const double *time,
     exchange_descent(&st);
     const int64_t U = st.have ? st.U : zmax;      /* some assignment inside both rows has a total <= U */
 
-    /* ladder of multiplier pairs as exact fractions L / S; pair 0 is (l1, l2) itself */
-    static const double step[5] = {1.0, 0.5, 2.0, 0.25, 4.0};
+    /* ladder of multiplier pairs (steps of 5 % on either axis) as exact fractions L / S; pair 0 is (l1, l2) itself */
+    static const double step[5] = {1.0, 1.0 / 1.05, 1.05, 1.0 / 1.1025, 1.1025};
     for (int a = 0; a < 5; ++a)
         for (int b = 0; b < 5; ++b) {
             if ((a > 0 && l1 == 0.0) || (b > 0 && l2 == 0.0)) continue;

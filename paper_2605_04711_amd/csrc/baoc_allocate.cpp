@@ -3,19 +3,24 @@
 // exclusions of Sec. 3.2 and a canonical answer (lexicographically smallest
 // optimum of the integer image of the instance).
 //
-// Method: blocks are taken in index order and partial assignments are kept as
-// a list of states (objective Z, memory W, time T).  A state is dropped when
-//   - it cannot be completed within the budgets (suffix minima),
-//   - a Lagrangian bound of the remaining blocks shows it cannot reach the
-//     incumbent (weak duality, evaluated exactly in 128-bit integers for a few
-//     fixed multiplier pairs found on the LP dual of the whole instance), or
-//   - another state of the same level uses no more of either resource and is
-//     better in (Z, lexicographic rank) -- any completion of the worse one is
-//     beaten by the same completion of the better one.
-// States of a level are generated in lexicographic order of their prefix, so
-// "lexicographic rank" is just the generation index.  The best final state is
-// the answer.  The list is capped by a node limit: when it is hit the call
-// fails rather than return a guess.
+// Method: a list recursion from the last block backwards, then the answer block by block.
+//   Lists.  lists[i] holds suffix states (Z, W, T) = sums of (phi, mem, tau) over some choice for
+//   the blocks i..N-1.  A state is dropped when
+//     - no prefix can complete it within the budgets (least use of each row by the blocks before i),
+//     - a Lagrangian bound of the blocks before i shows that no completion reaches the cutoff (weak
+//       duality, decided in floating point and, on a near miss, exactly in 128-bit integers, for a small
+//       grid of multiplier pairs around the maximiser of the dual of the whole instance), or
+//     - another state of the same level is no larger in all of Z, W and T: whatever completes the worse
+//       one completes the better one too, with a total no larger.
+//   A row that no prefix can push over its budget any more does not constrain a state: its use is
+//   raised to that threshold, so that more states undercut each other.
+//   Cutoffs rise from the smallest lattice value the bound of the whole instance allows (all totals lie
+//   on base + g Z, g the gcd of the phi differences inside the blocks): a run that ends empty proves that
+//   the optimum lies above its cutoff; the first run that reaches level 0 holds the optimum Z*.
+//   Answer.  The lists of that run hold, for every optimal assignment and every i, a state that undercuts
+//   its suffix.  So the lexicographically smallest optimum is read off in index order: block i takes the
+//   smallest configuration for which some state of lists[i+1] completes the prefix to Z* within both rows.
+// The lists are capped by a node limit: when it is hit the call fails rather than return a guess.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -40,7 +45,7 @@ struct Instance {
 };
 
 thread_local uint64_t g_node_limit = 0;
-constexpr uint64_t kDefaultNodeLimit = 40'000'000ull;
+constexpr uint64_t kDefaultNodeLimit = 32'000'000ull;      // states kept over all levels (24 bytes each)
 
 inline double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
@@ -100,13 +105,14 @@ void consider(const Instance& I, const std::vector<uint32_t>& pick, Heuristic& H
     if (!H.have || Z < H.Z) { H.have = true; H.Z = Z; H.pick = pick; }
 }
 
-// Best single swap that lowers the objective and stays within both budgets, repeated.
+// Best single swap that lowers the objective and stays within both budgets, repeated (at most 64 times:
+// the incumbent only ends the rising cutoffs of solve(), it does not have to be good).
 void improve(const Instance& I, Heuristic& H)
 {
     if (!H.have) return;
     int64_t W = 0, T = 0;
     for (uint32_t i = 0; i < I.N; ++i) { const Item& it = I.items[i][H.pick[i]]; W += it.w; T += it.t; }
-    for (uint32_t round = 0; round < 4 * I.N + 16; ++round) {
+    for (uint32_t round = 0; round < 64; ++round) {
         int64_t best = 0; uint32_t bi = 0, bk = 0;
         for (uint32_t i = 0; i < I.N; ++i) {
             const Item& cur = I.items[i][H.pick[i]];
@@ -120,45 +126,6 @@ void improve(const Instance& I, Heuristic& H)
         const Item& cur = I.items[bi][H.pick[bi]]; const Item& it = I.items[bi][bk];
         W += it.w - cur.w; T += it.t - cur.t; H.Z += best; H.pick[bi] = bk;
     }
-}
-
-// Greedy descent from the unconstrained optimum: start from the least-risk configuration of every
-// block and, while a budget is exceeded, take the swap that buys the most relief per unit of added
-// risk (relief = reduction of the excess over both rows, each in units of its budget).
-void greedy_descent(const Instance& I, Heuristic& H)
-{
-    std::vector<uint32_t> pick(I.N);
-    int64_t W = 0, T = 0;
-    for (uint32_t i = 0; i < I.N; ++i) {
-        uint32_t b = 0;
-        for (uint32_t k = 1; k < I.items[i].size(); ++k)
-            if (I.items[i][k].phi < I.items[i][b].phi) b = k;
-        pick[i] = b; W += I.items[i][b].w; T += I.items[i][b].t;
-    }
-    const double n1 = 1.0 / std::max<double>(1.0, (double)I.B1), n2 = 1.0 / std::max<double>(1.0, (double)I.B2);
-    for (uint64_t guard = 0; (W > I.B1 || T > I.B2) && guard < (uint64_t)I.N * 64; ++guard) {
-        double best = -1.0; uint32_t bi = 0, bk = 0; bool any = false;
-        for (uint32_t i = 0; i < I.N; ++i) {
-            const Item& cur = I.items[i][pick[i]];
-            for (uint32_t k = 0; k < I.items[i].size(); ++k) {
-                const Item& it = I.items[i][k];
-                double relief = 0.0;
-                if (W > I.B1) relief += (double)std::min<int64_t>(cur.w - it.w, W - I.B1) * n1;
-                if (T > I.B2) relief += (double)std::min<int64_t>(cur.t - it.t, T - I.B2) * n2;
-                if (!(relief > 0.0)) continue;
-                const double cost = (double)std::max<int64_t>(it.phi - cur.phi, 0) + 1.0;
-                const double score = relief / cost;
-                if (!any || score > best) { any = true; best = score; bi = i; bk = k; }
-            }
-        }
-        if (!any) return;
-        const Item& cur = I.items[bi][pick[bi]]; const Item& it = I.items[bi][bk];
-        W += it.w - cur.w; T += it.t - cur.t; pick[bi] = bk;
-    }
-    Heuristic G;
-    consider(I, pick, G);
-    improve(I, G);
-    if (G.have && (!H.have || G.Z < H.Z)) H = G;
 }
 
 // Concave maximisation of the dual in one multiplier by bisection on the sign of the subgradient.
@@ -195,25 +162,37 @@ Multiplier to_integer(double l1, double l2)
     return m;
 }
 
-struct State { int64_t Z, W, T; uint32_t node; float slack; };   // node: arena index (parent, cfg); slack: cutoff - bound, scaled
-struct Node { uint32_t parent; uint32_t item; };
+// A suffix state: sums of (phi, mem, tau) over the blocks i..N-1 of some choice for them.
+struct State { int64_t Z, W, T; };
 
-struct Key { int64_t Z; uint32_t seq; };
-inline bool operator<(const Key& a, const Key& b) { return a.Z < b.Z || (a.Z == b.Z && a.seq < b.seq); }
+int64_t gcd64(int64_t a, int64_t b)
+{
+    if (a < 0) a = -a;
+    if (b < 0) b = -b;
+    while (b) { const int64_t t = a % b; a = b; b = t; }
+    return a;
+}
 
 int solve(const Instance& I, std::vector<uint32_t>& answer)
 {
     const uint32_t N = I.N;
-    // suffix minima of each resource, for feasibility
-    std::vector<int64_t> sufW(N + 1, 0), sufT(N + 1, 0);
-    for (int i = (int)N - 1; i >= 0; --i) {
-        int64_t mw = kInf64, mt = kInf64;
-        for (const Item& it : I.items[i]) { mw = std::min(mw, it.w); mt = std::min(mt, it.t); }
-        sufW[i] = sufW[i + 1] + mw; sufT[i] = sufT[i + 1] + mt;
+    // least and largest use of each row by the blocks before i (prefixes), for feasibility and for the clamp
+    std::vector<int64_t> preMinW(N + 1, 0), preMinT(N + 1, 0), preMaxW(N + 1, 0), preMaxT(N + 1, 0);
+    int64_t g = 0;                                     // all totals lie on one lattice base + g Z
+    for (uint32_t i = 0; i < N; ++i) {
+        int64_t lw = kInf64, lt = kInf64, hw = -kInf64, ht = -kInf64;
+        for (const Item& it : I.items[i]) {
+            lw = std::min(lw, it.w); lt = std::min(lt, it.t); hw = std::max(hw, it.w); ht = std::max(ht, it.t);
+            g = gcd64(g, it.phi - I.items[i][0].phi);
+        }
+        preMinW[i + 1] = preMinW[i] + lw; preMinT[i + 1] = preMinT[i] + lt;
+        preMaxW[i + 1] = preMaxW[i] + hw; preMaxT[i + 1] = preMaxT[i] + ht;
     }
-    if (sufW[0] > I.B1 || sufT[0] > I.B2) return BAOC_ERR_INFEASIBLE;
+    if (g == 0) g = 1;
+    if (preMinW[N] > I.B1 || preMinT[N] > I.B2) return BAOC_ERR_INFEASIBLE;
 
-    // multipliers: alternate the two one-dimensional dual maximisations a few times
+    // multipliers: alternate the two one-dimensional dual maximisations a few times, then polish the pair by a
+    // pattern search on the dual value (alternation alone can stall at a kink of the piecewise linear dual)
     Heuristic H;
     double l1 = 0.0, l2 = 0.0;
     for (int round = 0; round < 3; ++round) {
@@ -223,35 +202,58 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
         l1 = n1; l2 = n2;
         if (same) break;
     }
+    if (l1 < 1e29 && l2 < 1e29) {
+        double best = eval_lagrangian(I, l1, l2).value;
+        double r = 1.25;
+        for (int it = 0; it < 60 && r > 1.0005; ++it) {
+            double c1 = l1, c2 = l2, cv = best;
+            for (int a = -1; a <= 1; ++a)
+                for (int b = -1; b <= 1; ++b) {
+                    if ((a == 0 && b == 0) || (a && l1 == 0.0) || (b && l2 == 0.0)) continue;
+                    const double m1 = a == 0 ? l1 : (a > 0 ? l1 * r : l1 / r), m2 = b == 0 ? l2 : (b > 0 ? l2 * r : l2 / r);
+                    std::vector<uint32_t> pick;
+                    const double v = eval_lagrangian(I, m1, m2, &pick).value;
+                    consider(I, pick, H);
+                    if (v > cv) { cv = v; c1 = m1; c2 = m2; }
+                }
+            if (cv > best) { best = cv; l1 = c1; l2 = c2; }
+            else r = std::sqrt(r);
+        }
+    }
     improve(I, H);
-    greedy_descent(I, H);
 
+    // Bounds are taken under a small grid of multiplier pairs around the best pair (steps of 5 %): deeper in the
+    // recursion the pair that bounds a state best drifts with the budgets the state has left.
     std::vector<Multiplier> mult;
     mult.push_back(to_integer(l1, l2));
     mult.push_back(to_integer(0.0, 0.0));
-    if (l1 > 0) { mult.push_back(to_integer(l1 * 0.5, l2)); mult.push_back(to_integer(l1 * 2.0, l2)); mult.push_back(to_integer(l1, 0.0)); }
-    if (l2 > 0) { mult.push_back(to_integer(l1, l2 * 0.5)); mult.push_back(to_integer(l1, l2 * 2.0)); mult.push_back(to_integer(0.0, l2)); }
+    for (int a = -2; a <= 2; ++a)
+        for (int b = -2; b <= 2; ++b) {
+            if ((a == 0 && b == 0) || (a && l1 == 0.0) || (b && l2 == 0.0)) continue;
+            mult.push_back(to_integer(l1 * std::pow(1.05, a), l2 * std::pow(1.05, b)));
+        }
+    if (l1 > 0 && l2 > 0) { mult.push_back(to_integer(l1, 0.0)); mult.push_back(to_integer(0.0, l2)); }
     const size_t M = mult.size();
-    // sufRC[m][k] = sum over blocks >= k of the least reduced cost, minus the budget terms
-    std::vector<std::vector<i128>> sufRC(M, std::vector<i128>(N + 1));
+    // preRC[m][i] = sum over the blocks before i of the least reduced cost, minus the budget terms
+    std::vector<std::vector<i128>> preRC(M, std::vector<i128>(N + 1));
     for (size_t m = 0; m < M; ++m) {
-        sufRC[m][N] = -(mult[m].L1 * (i128)I.B1 + mult[m].L2 * (i128)I.B2);
-        for (int i = (int)N - 1; i >= 0; --i) {
+        preRC[m][0] = -(mult[m].L1 * (i128)I.B1 + mult[m].L2 * (i128)I.B2);
+        for (uint32_t i = 0; i < N; ++i) {
             i128 best = 0; bool first = true;
             for (const Item& it : I.items[i]) {
                 const i128 rc = (i128)it.phi * mult[m].S + mult[m].L1 * (i128)it.w + mult[m].L2 * (i128)it.t;
                 if (first || rc < best) { best = rc; first = false; }
             }
-            sufRC[m][i] = sufRC[m][i + 1] + best;
+            preRC[m][i + 1] = preRC[m][i] + best;
         }
     }
     // double images of the multipliers: a bound far from the cutoff is decided in floating point,
     // only a near miss is evaluated exactly
     std::vector<double> Sd(M), L1d(M), L2d(M);
-    std::vector<std::vector<double>> sufRCd(M, std::vector<double>(N + 1));
+    std::vector<std::vector<double>> preRCd(M, std::vector<double>(N + 1));
     for (size_t m = 0; m < M; ++m) {
         Sd[m] = (double)mult[m].S; L1d[m] = (double)mult[m].L1; L2d[m] = (double)mult[m].L2;
-        for (uint32_t i = 0; i <= N; ++i) sufRCd[m][i] = (double)sufRC[m][i];
+        for (uint32_t i = 0; i <= N; ++i) preRCd[m][i] = (double)preRC[m][i];
     }
     int64_t z_max = 0;                                 // no assignment costs more than this
     for (uint32_t i = 0; i < N; ++i) {
@@ -259,122 +261,123 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
         for (const Item& it : I.items[i]) mx = std::max(mx, it.phi);
         z_max += mx;
     }
-    const int64_t ub = H.have ? H.Z : z_max;
+    const int64_t ub = H.have ? H.Z : z_max;           // some feasible assignment has a total <= ub (or none exists)
 
     const uint64_t limit = g_node_limit ? g_node_limit : kDefaultNodeLimit;
-    std::vector<Node> arena;
-    std::vector<State> cur, nxt;
+    // lists[i]: suffix states of the blocks i..N-1 that some prefix may still complete to a feasible
+    // assignment of value <= cutoff, none of them undercut by another in all of (Z, W, T)
+    std::vector<std::vector<State>> lists(N + 1);
+    std::vector<State> cand;
     std::vector<uint32_t> order;
-    std::vector<uint8_t> dead;
-    std::vector<std::pair<int64_t, Key>> stair;        // (T, best key among kept states with time <= T), T ascending
+    std::vector<std::pair<int64_t, int64_t>> stair;    // (T, least Z among the states swept so far with time <= T), T ascending, Z descending
 
-    // run(cutoff, level_cap): build the state lists for this cutoff.  A run that ends with states
-    // has kept every prefix of every assignment of value <= cutoff that is not dominated.
-    enum { kRunOk = 0, kRunEmpty = 1, kRunCapped = 2, kRunLimit = 3 };
-    std::vector<float> slacks;
-    auto run = [&](int64_t cutoff, size_t level_cap, size_t beam) -> int {
-        arena.clear();
-        arena.push_back({0xffffffffu, 0});
-        cur.assign(1, State{0, 0, 0, 0, 0.f});
-        bool empty = false;
-        for (uint32_t i = 0; i < N && !empty; ++i) {
-            nxt.clear();
-            for (const State& s : cur) {
-                for (uint32_t k = 0; k < I.items[i].size(); ++k) {
-                    const Item& it = I.items[i][k];
-                    State c{s.Z + it.phi, s.W + it.w, s.T + it.t, 0, 0.f};
-                    if (c.W + sufW[i + 1] > I.B1 || c.T + sufT[i + 1] > I.B2) continue;
+    enum { kRunOk = 0, kRunEmpty = 1, kRunLimit = 3 };
+    // run(cutoff): build the lists from the last block backwards.  A run that ends with states at level 0
+    // has kept, for every feasible assignment of value <= cutoff and every i, a state of lists[i] that
+    // undercuts (or equals) its suffix i..N-1.
+    auto run = [&](int64_t cutoff) -> int {
+        uint64_t total = 1;
+        lists[N].assign(1, State{0, 0, 0});
+        for (int i = (int)N - 1; i >= 0; --i) {
+            // A row that no prefix can push over its budget any more is not a constraint for the state: below
+            // the threshold every value is as good as the threshold itself, which lets more states undercut others.
+            const int64_t floorW = I.B1 - preMaxW[i], floorT = I.B2 - preMaxT[i];
+            cand.clear();
+            for (const State& s : lists[i + 1]) {
+                for (const Item& it : I.items[i]) {
+                    State c{s.Z + it.phi, std::max(s.W + it.w, floorW), std::max(s.T + it.t, floorT)};
+                    if (c.W + preMinW[i] > I.B1 || c.T + preMinT[i] > I.B2) continue;
                     bool cut = false;
                     for (size_t m = 0; m < M && !cut; ++m) {
                         const double a = (double)c.Z * Sd[m], b = L1d[m] * (double)c.W, d = L2d[m] * (double)c.T;
-                        const double lhs_d = a + b + d + sufRCd[m][i + 1], rhs_d = (double)cutoff * Sd[m];
-                        if (m == 0) c.slack = (float)((rhs_d - lhs_d) / Sd[0]);
-                        const double tol = 1e-9 * (std::fabs(a) + b + std::fabs(d) + std::fabs(sufRCd[m][i + 1]) + std::fabs(rhs_d));
+                        const double lhs_d = a + b + d + preRCd[m][i], rhs_d = (double)cutoff * Sd[m];
+                        const double tol = 1e-9 * (std::fabs(a) + std::fabs(b) + std::fabs(d) + std::fabs(preRCd[m][i]) + std::fabs(rhs_d));
                         if (lhs_d > rhs_d + tol) { cut = true; break; }
                         if (lhs_d < rhs_d - tol) continue;
-                        const i128 lhs = (i128)c.Z * mult[m].S + mult[m].L1 * (i128)c.W + mult[m].L2 * (i128)c.T + sufRC[m][i + 1];
+                        const i128 lhs = (i128)c.Z * mult[m].S + mult[m].L1 * (i128)c.W + mult[m].L2 * (i128)c.T + preRC[m][i];
                         cut = lhs > (i128)cutoff * mult[m].S;
                     }
                     if (cut) continue;
-                    if (arena.size() >= limit || arena.size() >= 0xfffffff0ull) return kRunLimit;
-                    c.node = (uint32_t)arena.size();
-                    arena.push_back({s.node, k});
-                    nxt.push_back(c);
+                    cand.push_back(c);
                 }
             }
-            if (nxt.empty()) { empty = true; break; }
-            // dominance: sweep by (W, T, key); staircase over T of the best key seen
-            const size_t n = nxt.size();
-            if (n > 1) {
-                order.resize(n);
-                for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
-                std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-                    const State &x = nxt[a], &y = nxt[b];
-                    if (x.W != y.W) return x.W < y.W;
-                    if (x.T != y.T) return x.T < y.T;
-                    if (x.Z != y.Z) return x.Z < y.Z;
-                    return a < b;
-                });
-                dead.assign(n, 0);
-                stair.clear();
-                for (uint32_t j : order) {
-                    const State& s = nxt[j];
-                    const Key key{s.Z, j};
-                    // first entry with T > s.T; the one before it holds the best key with time <= s.T
-                    auto it = std::upper_bound(stair.begin(), stair.end(), s.T,
-                                               [](int64_t t, const std::pair<int64_t, Key>& e) { return t < e.first; });
-                    if (it != stair.begin() && std::prev(it)->second < key) { dead[j] = 1; continue; }
-                    if (it != stair.begin() && std::prev(it)->first == s.T) {
-                        --it;
-                        it->second = key;
-                    } else {
-                        it = stair.insert(it, std::make_pair(s.T, key));
-                    }
-                    auto nx = std::next(it), e = nx;
-                    while (e != stair.end() && !(e->second < key)) ++e;   // entries to the right that are no better
-                    stair.erase(nx, e);
-                }
-                size_t o = 0;
-                for (size_t j = 0; j < n; ++j)
-                    if (!dead[j]) nxt[o++] = nxt[j];
-                nxt.resize(o);
+            if (cand.empty()) return kRunEmpty;
+            // keep what nothing undercuts: sweep by (W, T, Z) with a staircase over T of the least Z seen
+            const size_t n = cand.size();
+            std::vector<State>& out = lists[i];
+            out.clear();
+            order.resize(n);
+            for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
+            std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+                const State &x = cand[a], &y = cand[b];
+                if (x.W != y.W) return x.W < y.W;
+                if (x.T != y.T) return x.T < y.T;
+                return x.Z < y.Z;
+            });
+            stair.clear();
+            for (uint32_t j : order) {
+                const State& s = cand[j];
+                // first entry with T > s.T; the one before it holds the least Z among swept states with time <= s.T
+                auto it = std::upper_bound(stair.begin(), stair.end(), s.T,
+                                           [](int64_t t, const std::pair<int64_t, int64_t>& e) { return t < e.first; });
+                if (it != stair.begin() && std::prev(it)->second <= s.Z) continue;      // undercut (or equalled)
+                if (it != stair.begin() && std::prev(it)->first == s.T) { --it; it->second = s.Z; }
+                else it = stair.insert(it, std::make_pair(s.T, s.Z));
+                auto nx = std::next(it), e = nx;
+                while (e != stair.end() && e->second >= s.Z) ++e;                        // entries to the right that are no better
+                stair.erase(nx, e);
+                out.push_back(s);
             }
-            if (beam && nxt.size() > beam) {              // heuristic mode: keep the most promising states
-                slacks.resize(nxt.size());
-                for (size_t j = 0; j < nxt.size(); ++j) slacks[j] = nxt[j].slack;
-                std::nth_element(slacks.begin(), slacks.begin() + (nxt.size() - beam), slacks.end());
-                const float thr = slacks[nxt.size() - beam];
-                size_t o = 0;
-                for (size_t j = 0; j < nxt.size() && o < beam; ++j)
-                    if (nxt[j].slack >= thr) nxt[o++] = nxt[j];
-                nxt.resize(o);
-            }
-            cur.swap(nxt);
-            if (cur.size() > level_cap) return kRunCapped;
+            total += out.size();
+            if (total > limit) return kRunLimit;
         }
-        return empty ? kRunEmpty : kRunOk;
+        return kRunOk;
     };
-    // First try the incumbent itself as cutoff: the heuristics usually land within 1e-4 of the
-    // optimum and then one pass is all there is.  If the lists grow large the incumbent was poor:
-    // a beam-limited pass of the same recursion finds a better one, then the exact pass is repeated.
-    const size_t no_cap = std::numeric_limits<size_t>::max();
-    int64_t cut = ub;
-    int rc = run(cut, 20000, 0);
-    if (rc == kRunCapped) {
-        rc = run(cut, no_cap, 1024);
-        if (rc == kRunOk)
-            for (const State& st : cur) cut = std::min(cut, st.Z);
-        rc = run(cut, no_cap, 0);
+    auto best_final = [&]() {                          // least Z among the states of level 0 (all of them are feasible)
+        int64_t z = kInf64;
+        for (const State& s : lists[0]) z = std::min(z, s.Z);
+        return z;
+    };
+
+    // Cutoffs rise from the smallest lattice value that the bound of the whole instance allows towards the
+    // incumbent: a run that ends empty proves that the optimum lies above its cutoff, the first run that reaches
+    // level 0 holds the optimum.  The distance from the bound grows by half each time, so the last run looks at a
+    // window at most 1.5 times wider than the one the optimum needs, however poor the incumbent is (the number of
+    // surviving states grows steeply with that width), and the empty runs before it are cheap.
+    int64_t low = ub;
+    {
+        const i128 room = (i128)ub * mult[0].S - preRC[0][N];                  // S (ub - bound of the whole instance)
+        if (room > 0) low = ub - (int64_t)(room / (mult[0].S * (i128)g)) * g;
+    }
+    int rc;
+    {
+        const int64_t span = (ub - low) / g;               // lattice steps from low to the incumbent
+        int64_t at = 0, step = std::max<int64_t>(1, span >> 20);
+        for (;;) {
+            rc = run(low + at * g);
+            if (rc != kRunEmpty || at >= span) break;
+            at = std::min(span, at + step);
+            step = std::max(step + 1, step + step / 2);
+        }
     }
     if (rc == kRunLimit) return BAOC_ERR_LIMIT;
     if (rc == kRunEmpty) return BAOC_ERR_INFEASIBLE;
-    // best final state: least Z, then earliest in lexicographic order
-    size_t best = 0;
-    for (size_t j = 1; j < cur.size(); ++j)
-        if (cur[j].Z < cur[best].Z) best = j;
+
+    // The canonical optimum, block by block: the smallest configuration index for which some kept suffix
+    // state still completes the prefix to the optimal value within both budgets.
+    const int64_t z_star = best_final();
     answer.assign(N, 0);
-    uint32_t node = cur[best].node;
-    for (int i = (int)N - 1; i >= 0; --i) { answer[i] = I.items[i][arena[node].item].cfg; node = arena[node].parent; }
+    int64_t Zp = 0, Wp = 0, Tp = 0;
+    for (uint32_t i = 0; i < N; ++i) {
+        bool placed = false;
+        for (const Item& it : I.items[i]) {            // ascending configuration index
+            const int64_t z = Zp + it.phi, w = Wp + it.w, t = Tp + it.t;
+            for (const State& s : lists[i + 1])
+                if (z + s.Z <= z_star && w + s.W <= I.B1 && t + s.T <= I.B2) { placed = true; break; }
+            if (placed) { answer[i] = it.cfg; Zp = z; Wp = w; Tp = t; break; }
+        }
+        if (!placed) return BAOC_ERR_LIMIT;            // cannot happen: the lists hold a witness for every step
+    }
     return BAOC_OK;
 }
 

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from synth import workloads as W
-from test_gpu_parity import env, run_both  # noqa: F401
+from test_gpu_parity import check_allocation, env, run_both  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -33,8 +33,9 @@ def test_fullsize_sampled_blocks(env, name, T):  # noqa: F811
     print(f"{name}: oracle follows {len(only)} of {len(w.blocks)} blocks, "
           f"{sum(w.blocks[i].numel for i in only):,} of {w.numel:,} coordinates, T={T}", flush=True)
     torch = env["torch"]
-    run_both(env, w, T, only=only, check_state=True,
-             theta_dtype=torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32)
+    prof, stats, risk, ostats, orisk = run_both(env, w, T, only=only, check_state=True,
+                                                theta_dtype=torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32)
+    check_allocation(env, w, risk)                      # the full risk table of the device run, all blocks
 
 
 def test_blocks_beyond_2_to_the_31_coordinates(env):  # noqa: F811

@@ -101,9 +101,21 @@ def test_launch_shapes_leave_the_results_alone(env, dtype, shape):
     run_both(env, ragged_workload(dtype, 1), 4, theta_dtype=env["torch"].float32, **shape)
 
 
+def check_allocation(env, w, risk):
+    """The GPU-produced risk table through both solvers of Eq. 2: same answer, bit for bit."""
+    B = env["B"]
+    mem, tc, bm, cap = W.allocation_inputs(w)
+    cap = 1.3 * len(w.blocks) if not np.isfinite(cap) else cap
+    x, obj, m, t = B.allocate(risk, mem, tc, bm, cap)
+    rc, ox, oobj, om, ot = oracle.allocate_bnb(risk, mem, tc, bm, cap)
+    assert rc == 0 and list(x) == list(ox) and (obj, m, t) == (oobj, om, ot), w.name
+    assert m <= bm and t <= cap + 1e-9
+
+
 def test_resnet50_all_blocks_all_steps(env):
     w = W.make("resnet50")
-    run_both(env, w, w.T, theta_dtype=env["torch"].float32)
+    prof, stats, risk, ostats, orisk = run_both(env, w, w.T, theta_dtype=env["torch"].float32)
+    check_allocation(env, w, risk)
 
 
 def test_gpt2_small_all_steps(env):

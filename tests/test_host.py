@@ -222,6 +222,73 @@ def test_allocate_full_size_instances_properties(name):
         assert obj <= ip.fun + 1e-6 and obj >= ip.fun - 1e-5 * max(1.0, abs(ip.fun))
 
 
+@pytest.mark.parametrize("name", ["resnet50", "llama7b", "gpt_1p3b", "unet"])
+@pytest.mark.parametrize("K", [6, 21])
+def test_allocate_full_size_grid_is_fast_and_canonical(name, K):
+    """N in {161, 291, 292, 686} x K in {6, 21}, the layouts' real state bytes, time cap 1.3 N, and risk tables from
+    continuous to tie-heavy (integer-valued, all zero, rounded to 1 and 3 decimals, saturated App. A signals; the
+    '+' families make the memory budget bind).  Every cell: BAOC_OK in under a second (Sec. 3.2's remark on the
+    solve time) and the choice vector bit-identical to the oracle's depth-first branch and bound, which reaches every
+    cell of this grid (slowest: llama7b x 21, a few seconds per family)."""
+    import time
+    import alloc_families as F
+    w, cfgs, mem, tc, bm, cap = F.costs(name, K)
+    N = len(w.blocks)
+    for j, kind in enumerate(F.KINDS):
+        rng = np.random.default_rng([N, K, j])
+        risk = F.family(rng, kind, N, cfgs, mem)
+        t0 = time.perf_counter()
+        x, obj, m, t = B.allocate(risk, mem, tc, bm, cap)
+        dt = time.perf_counter() - t0
+        assert dt < 1.0, (name, K, kind, dt)
+        ref = oracle.allocate_bnb(risk, mem, tc, bm, cap, node_limit=400_000_000)
+        assert ref[0] == 0, (name, K, kind, "oracle did not finish")
+        assert list(x) == list(ref[1]) and (obj, m, t) == tuple(ref[2:]), (name, K, kind)
+
+
+# Both rows binding, generic (measured-like) time costs, exclusions: harder for both solvers.  Cells where the
+# oracle's search exceeds its node limit are parity unpinned for the choice vector; there the answer must still
+# be feasible and no worse than what a library MILP solver finds.
+HARD = [("unet", 6, "saturated", 0.3, 0.8, 1, False), ("unet", 21, "saturated", 0.3, 0.5, 1, False),
+        ("resnet50", 6, "integer+", 0.2, 1.0, 2, True), ("gpt_1p3b", 6, "saturated", 0.2, 0.8, 2, False),
+        ("resnet50", 21, "saturated", 0.1, 0.5, 1, True),
+        # the oracle gives up on these three within its node limit: choice vectors parity unpinned
+        ("resnet50", 6, "signals", 0.2, 0.8, 1, False), ("llama7b", 6, "signals", 0.3, 1.0, 1, False),
+        ("resnet50", 21, "round3", 0.1, 1.0, 1, True)]
+
+
+@pytest.mark.parametrize("name,K,kind,ratio,capf,tmode,excl", HARD)
+def test_allocate_both_rows_binding(name, K, kind, ratio, capf, tmode, excl):
+    from scipy.optimize import Bounds, LinearConstraint, milp
+    from scipy.sparse import csr_matrix, eye, kron
+    import alloc_families as F
+    w, cfgs, mem, tc, _, _ = F.costs(name, K)
+    N = len(w.blocks)
+    rng = np.random.default_rng([N, K, int(ratio * 100), int(capf * 10), tmode])
+    risk = F.family(rng, kind, N, cfgs, mem)
+    bm, cap = int(ratio * 8 * w.numel), capf * N
+    if tmode:
+        tc = tc * (1 + 0.2 * rng.random(tc.shape))
+    if tmode == 2:
+        tc = np.round(tc, 2)
+    fb = (rng.random((N, K)) < 0.1).astype(np.uint8) if excl else None
+    x, obj, m, t = B.allocate(risk, mem, tc, bm, cap, fb)
+    assert m <= bm and t <= cap + 1e-9 and (fb is None or not any(fb[i, x[i]] for i in range(N)))
+    ref = oracle.allocate_bnb(risk, mem, tc, bm, cap, fb, node_limit=5_000_000)
+    if ref[0] == 0:
+        assert list(x) == list(ref[1]) and (obj, m, t) == tuple(ref[2:])
+    else:
+        assert ref[0] == oracle.ORC_TOO_BIG                                       # parity unpinned for this cell
+        ub = np.ones(N * K) if fb is None else 1.0 - fb.reshape(-1)
+        cons = [LinearConstraint(kron(eye(N), np.ones((1, K)), format="csr"), 1, 1),
+                LinearConstraint(csr_matrix(mem.reshape(1, -1).astype(float)), -np.inf, bm),
+                LinearConstraint(csr_matrix(tc.reshape(1, -1)), -np.inf, cap)]
+        ip = milp(risk.reshape(-1), constraints=cons, integrality=np.ones(N * K), bounds=Bounds(0, ub),
+                  options=dict(mip_rel_gap=0.0, time_limit=60))
+        if ip.success and ip.status == 0:
+            assert obj <= ip.fun + 1e-6
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU only: `bench.py --gpus N` with N > 1 exits with a message that says so."""
     import subprocess
