@@ -34,6 +34,8 @@ def assert_stats_close(got, want, where=""):
         if np.isnan(w) or np.isnan(g):
             assert np.isnan(w) and np.isnan(g), f"{where} {f}: {g} vs {w}"
             continue
+        if g == w:                                       # also equal infinities (after a non-finite gradient)
+            continue
         assert abs(g - w) <= ATOL + RTOL * abs(w), f"{where} {f}: gpu {g!r} oracle {w!r} diff {abs(g - w):.3e}"
 
 

@@ -38,6 +38,15 @@ def test_fullsize_sampled_blocks(env, name, T):  # noqa: F811
     check_allocation(env, w, risk)                      # the full risk table of the device run, all blocks
 
 
+@pytest.mark.parametrize("seed", [2, 3])
+def test_fullsize_unet_other_seeds(env, seed):  # noqa: F811
+    """The UNet-shaped layout on the streams of seeds 2 and 3 (three seeds in all; seed 1 is the headline)."""
+    w = W.make("unet", seed=seed)
+    only = sample_blocks(w, seed=11 + seed)
+    prof, stats, risk, ostats, orisk = run_both(env, w, 4, only=only, check_state=True, seed=seed, theta_dtype=env["torch"].float32)
+    check_allocation(env, w, risk)
+
+
 def test_blocks_beyond_2_to_the_31_coordinates(env):  # noqa: F811
     """One vector block and one matrix block of more than 2^31 coordinates each, fed a constant gradient: the
     intensive statistics equal those of a small oracle block on the same gradient and the extensive ones scale

@@ -386,6 +386,43 @@ def test_nan_gradient_poisons_only_its_block(env):
     assert_stats_close(s[0], o.finalize(), "nan block")
 
 
+def test_infinite_gradients_poison_only_their_block(env):
+    """+inf and -inf coordinates in one block: its sums come out infinite or NaN exactly as in the oracle (NaN
+    cosines and NaN Q count as 0), the quantiles still rank the finite second moments, the other block is untouched."""
+    torch, binding = env["torch"], env["binding"]
+    blocks = [(0, 1000), (1024, 1000)]
+    clean = torch.randn(2048, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(5))
+    g = clean.clone(); g[5] = float("inf"); g[300] = float("-inf")
+    a, ref = binding.Profiler(blocks), binding.Profiler(blocks)
+    for _ in range(2):
+        a.step(g); ref.step(clean)
+    s, r = a.finalize()[0], ref.finalize()[0]
+    assert np.isinf(s[0].m_sq) and np.isinf(s[0].v_l1) and np.isfinite(s[0].q90) and np.isfinite(s[0].A)
+    assert bytes(s[1]) == bytes(r[1])                      # the neighbour does not notice
+    o = oracle.Block(1000); h = to_host_bits(g[:1000]); o.step(h); o.step(h)
+    assert_stats_close(s[0], o.finalize(), "inf block")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_window_of_a_single_step(env, dtype):
+    """finalize after the first step: the statistics come from the launch that does not read the states
+    (no cosine yet, rho_bar = 0), F and C from v after one step."""
+    torch = env["torch"]
+    prof, stats, risk, ostats, orisk = run_both(env, ragged_workload(dtype, 1), 1,
+                                                theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
+    assert all(st.steps == 1 and st.n_cos == 0 and st.rho_bar == 0.0 for st in stats)
+
+
+@pytest.mark.parametrize("seed", [2, 3])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_blocks_other_seeds(env, dtype, seed):
+    """The ragged layout on the streams of seeds 2 and 3 (stream parameters and noise both drawn from the seed)."""
+    torch = env["torch"]
+    w = ragged_workload(dtype, 1)
+    W.draw_stream_params(w, seed)
+    run_both(env, w, 5, seed=seed, theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
+
+
 def test_error_paths(env):
     torch, binding = env["torch"], env["binding"]
     prof = binding.Profiler([(0, 100), (200, 50)])
