@@ -22,6 +22,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "baoc_internal.h"
@@ -454,9 +455,12 @@ __global__ __launch_bounds__(256) void k_block_reduce(
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 4: exact order statistics of v per block by a three-pass radix selection
+// Eq. 4: exact order statistics of v per block by a three-digit radix selection
 // on the bit patterns (v >= 0, so the pattern order is the value order).
-// Digits: bits 30..20, 19..9, 8..0.  Four ranks per block share every pass.
+// Digits: bits 30..19, 18..8, 7..0.  Four ranks per block share every pass.
+// Matrix blocks read v twice only: the pass that counts the second digit also
+// writes the few coordinates that carry a selected first digit into a candidate
+// list, and the third digit is counted on that list.
 // ---------------------------------------------------------------------------
 
 // Chunk table from the block rows (one thread per chunk; the owning block by bisection on
@@ -490,13 +494,17 @@ __global__ void k_fill_u32(uint32_t* p, uint64_t n, uint32_t val)
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) p[i] = val;
 }
 
-constexpr uint32_t kBins = 2048;
+constexpr uint32_t kBins = 2048;          // words of one rank's histogram; a block owns four of them
+constexpr uint32_t kBits2 = 11, kBits3 = 8;                       // 12 + 11 + 8 bits of the 31-bit key
+constexpr uint32_t kShift1 = kBits2 + kBits3, kShift2 = kBits3;   // key >> kShift1: first digit; key >> kShift2: first two
+constexpr uint32_t kBins1 = 1u << (31 - kShift1), kBins2 = 1u << kBits2, kBins3 = 1u << kBits3;
+static_assert(kBins1 == 2 * kBins && kBins2 == kBins, "the first-digit histogram fills two of a block's four slots");
 
 // The four ranks of a block usually share their key prefix pairwise (lo and lo+1 of a quantile fall
 // into one bin).  Elements are matched against the distinct prefixes only; slot_of[t] names the LDS
 // histogram that serves rank t, and the flush adds it to every rank that shares it.
 struct Prefixes { uint32_t pre[4]; uint32_t slot_of[4]; uint32_t n; };
-constexpr uint32_t kNoPrefix = 0xffffffffu;             // never equals a key prefix (at most 22 bits)
+constexpr uint32_t kNoPrefix = 0xffffffffu;             // never equals a key prefix (at most 23 bits)
 __device__ __forceinline__ Prefixes distinct_prefixes(const uint32_t* __restrict__ sel_prefix, uint32_t block)
 {
     // fully unrolled with static indices so that everything stays in (scalar) registers
@@ -544,12 +552,15 @@ constexpr uint32_t kHistGrid = 2048;     // persistent workgroups of the histogr
 template <int PASS>
 __global__ __launch_bounds__(256) void k_hist(
     const float* __restrict__ v_all, const Chunk* __restrict__ chunks, const uint32_t* __restrict__ list,
-    uint32_t n_chunks, const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all)
+    uint32_t n_chunks, const uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ hist_all,
+    const BlockRow* __restrict__ rows, const uint32_t* __restrict__ scan3)
 {
-    // list == nullptr: every chunk; otherwise the chunks named by list[0 .. n_chunks)
+    // list == nullptr: every chunk; otherwise the chunks named by list[0 .. n_chunks).
+    // scan3 (third pass over every chunk only): blocks whose flag is 0 have had their last digit counted on
+    // their candidate lists and are skipped, a whole block per iteration.
     typedef uint32_t u4 __attribute__((ext_vector_type(4)));
     constexpr int NT = PASS == 1 ? 1 : 4;
-    constexpr uint32_t NB = PASS == 3 ? 512 : kBins;
+    constexpr uint32_t NB = PASS == 1 ? kBins1 : (PASS == 2 ? kBins2 : kBins3);
     __shared__ uint32_t h[NT * NB];
     const uint32_t per = (n_chunks + gridDim.x - 1) / gridDim.x;
     const uint32_t c0 = blockIdx.x * per, c1 = min(n_chunks, c0 + per);
@@ -584,8 +595,12 @@ __global__ __launch_bounds__(256) void k_hist(
     };
     load_prefixes();
     __syncthreads();
-    for (uint32_t c = c0; c < c1; ++c) {
+    for (uint32_t c = c0; c < c1;) {
         const Chunk ck = chunks[list ? list[c] : c];
+        if (PASS == 3 && scan3 && !scan3[ck.block]) {        // chunk ids of a block are consecutive (list == nullptr here)
+            c = rows[ck.block].first_chunk + rows[ck.block].n_chunks;
+            continue;
+        }
         if (ck.block != cur) { flush(); cur = ck.block; load_prefixes(); }
         const uint32_t* bits = reinterpret_cast<const uint32_t*>(v_all + ck.state_start);
         for (uint32_t e0 = threadIdx.x * 4; e0 < ck.count; e0 += 4096) {
@@ -602,15 +617,16 @@ __global__ __launch_bounds__(256) void k_hist(
                 for (int j = 0; j < 4; ++j) {
                     if (e + j >= ck.count) break;
                     if (PASS == 1) {
-                        atomicAdd(&h[key[j] >> 20], 1u);
+                        atomicAdd(&h[key[j] >> kShift1], 1u);
                     } else {
-                        const uint32_t hi = PASS == 2 ? key[j] >> 20 : key[j] >> 9;
-                        const uint32_t bin = PASS == 2 ? (key[j] >> 9) & 0x7ffu : key[j] & 0x1ffu;
+                        const uint32_t hi = PASS == 2 ? key[j] >> kShift1 : key[j] >> kShift2;
+                        const uint32_t bin = PASS == 2 ? (key[j] >> kShift2) & (kBins2 - 1) : key[j] & (kBins3 - 1);
                         count_match(h, d, NB, hi, bin);
                     }
                 }
             }
         }
+        ++c;
     }
     flush();
 }
@@ -621,12 +637,16 @@ __global__ __launch_bounds__(256) void k_hist(
 template <int PASS>
 __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_all, const BlockRow* __restrict__ rows,
                                              uint32_t* __restrict__ sel_prefix, uint32_t* __restrict__ sel_rank,
-                                             float* __restrict__ order_stat)
+                                             float* __restrict__ order_stat, uint32_t* __restrict__ scan3)
 {
-    constexpr uint32_t NB = PASS == 3 ? 512 : kBins, PER = NB / 64;
+    constexpr uint32_t NB = PASS == 1 ? kBins1 : (PASS == 2 ? kBins2 : kBins3), PER = NB / 64;
     const uint32_t id = blockIdx.x, b = id >> 2, t = id & 3, lane = threadIdx.x;
+    // the first-digit histogram is shared by the four ranks and fills the block's first two slots
     const uint32_t* h = hist_all + ((uint64_t)b * 4 + (PASS == 1 ? 0 : t)) * kBins + lane * PER;
     const uint32_t r = PASS == 1 ? (uint32_t)rows[b].rank[t] : sel_rank[id];
+    // Blocks walked chunk-wise have their last digit counted by a third scan; matrix blocks only if
+    // a candidate list overflows (set by the second tile pass).
+    if (PASS == 1 && t == 0 && lane == 0) scan3[b] = rows[b].vec_first != kNoVec;
     uint32_t cnt[PER], mine = 0;
 #pragma unroll
     for (uint32_t i = 0; i < PER; ++i) { cnt[i] = h[i]; mine += cnt[i]; }
@@ -650,7 +670,7 @@ __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_a
             }
         }
         bin += lane * PER;
-        const uint32_t prefix = PASS == 1 ? bin : ((sel_prefix[id] << (PASS == 2 ? 11 : 9)) | bin);
+        const uint32_t prefix = PASS == 1 ? bin : ((sel_prefix[id] << (PASS == 2 ? kBits2 : kBits3)) | bin);
         sel_prefix[id] = prefix;
         sel_rank[id] = rr;
         if (PASS == 3) order_stat[id] = __builtin_bit_cast(float, prefix);
@@ -664,27 +684,30 @@ __global__ __launch_bounds__(64) void k_pick(const uint32_t* __restrict__ hist_a
 //   pass 1: row / column partial sums (Eq. 7), sum of p = 1/(sqrt(v)+eps) (Eq. 6), first
 //           radix digit histogram (Eq. 4)
 //   pass 2: |S - r c^T / mu|^2 and |S|^2 (Eq. 7), ((p/p-bar - 1) theta)^2 and theta^2 (Eq. 6),
-//           second digit histogram
+//           second digit histogram, and the keys that carry a selected first digit appended to the
+//           task's candidate list (the last digit is then counted on the lists, k_cand_hist3)
+// Full tiles on the vector path load their rows one round ahead of their use.
 // Blocks without a matrix shape are walked chunk-wise by k_hist / k_distortion instead.
 // ---------------------------------------------------------------------------
 
 constexpr uint32_t kTileRows = 256, kTileCols = 256;
-// Rows a wavefront loads before it consumes them.  Measured on the 7B layout (whole finalize): 1 row 22.7 ms,
-// 2 rows 19.9, 4 rows 20.5, 8 rows 23.0 -- as in the step kernel, more requests in flight are not better.
-constexpr uint32_t kRowsInFlight = 2;
 
 struct alignas(8) MatRow {
     uint64_t state_start;                 // first coordinate of the block in v
     uint64_t grad_start;                  // the block's offset in the caller's flat buffers (theta)
     uint64_t off_r, off_c;                // into the r / c vectors (floats)
     uint64_t off_rowpart, off_colpart;    // into the partial-sum arrays (floats)
+    uint64_t cand_base;                   // the block's first candidate list (words into the candidate buffer)
     uint32_t rows, cols, n_tiles, n_segs;
-    uint32_t first_task, first_quad, block, pad_;
+    uint32_t first_task, first_quad, block;
+    uint32_t cand_cap;                    // words per candidate list (one list per task)
 };
 
 struct MatTask { uint32_t mat, task, row0, row1, col0, ncols, tile, seg; bool vec, valid; };
 
 // Workgroup `quad` -> its block and this wavefront's task (tile index fastest).
+// `wave` must be uniform over the wavefront (callers pass it through readfirstlane), so that the task and
+// every address derived from it live in scalar registers.
 __device__ __forceinline__ MatTask decode_quad(const MatRow* __restrict__ mats, uint32_t n_mats, uint32_t quad, uint32_t wave)
 {
     uint32_t lo = 0, hi = n_mats - 1;
@@ -744,14 +767,21 @@ __device__ __forceinline__ void load_tile_theta(const typename GradIO<TT>::elem*
     }
 }
 
+__device__ __forceinline__ uint32_t scalar_wave_index()
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+}
+
+constexpr int kRowsAhead = 2;             // rows of a full tile loaded per round, one round ahead of their use
+
 __global__ __launch_bounds__(256) void k_tile_pass1(
     const float* __restrict__ v_all, const MatRow* __restrict__ mats, uint32_t n_mats,
     float* __restrict__ rowpart, float* __restrict__ colpart, float* __restrict__ psumpart,
     uint32_t* __restrict__ hist_all, float eps, bool want_p)
 {
-    __shared__ uint32_t h[kBins];
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    for (uint32_t i = threadIdx.x; i < kBins; i += 256) h[i] = 0;
+    __shared__ uint32_t h[kBins1];
+    const uint32_t lane = threadIdx.x & 63u, wave = scalar_wave_index();
+    for (uint32_t i = threadIdx.x; i < kBins1; i += 256) h[i] = 0;
     const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
     const MatRow& m = mats[t.mat];
     __syncthreads();
@@ -764,13 +794,14 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
         // v (rank one, p constant) comes out as such to ~1e-7 instead of the ~1e-5 of a long fp32 chain.
         double cs[4] = {0.0, 0.0, 0.0, 0.0}, psum = 0.0;
         float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
-        auto consume = [&](const float x[4]) {
+        auto consume = [&](auto full, const float x[4]) {
+            constexpr bool FULL = decltype(full)::value;     // every column of the lane is inside the tile
             float prow = 0.f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 cs[k] += (double)x[k];
-                if (ok[k]) {
-                    atomicAdd(&h[(__builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu) >> 20], 1u);
+                if (FULL || ok[k]) {
+                    atomicAdd(&h[(__builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu) >> kShift1], 1u);
                     if (want_p) prow += __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
                 }
             }
@@ -778,23 +809,38 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
             return wave_sum((x[0] + x[1]) + (x[2] + x[3]));
         };
         uint32_t r = t.row0;
-        for (; r + kRowsInFlight <= t.row1; r += kRowsInFlight) {
-            float x[kRowsInFlight][4];
+        if (t.vec && t.ncols == kTileCols) {
+            const float* vp = row + 4 * lane;
+            f4 nx[kRowsAhead];
 #pragma unroll
-            for (int q = 0; q < (int)kRowsInFlight; ++q) load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
+            for (int q = 0; q < kRowsAhead; ++q) nx[q] = f4{0.f, 0.f, 0.f, 0.f};
+            auto issue = [&](uint32_t r0) {
 #pragma unroll
-            for (int q = 0; q < (int)kRowsInFlight; ++q) {
-                const float rs = consume(x[q]);
-                if (lane == 0) rp[(uint64_t)q * m.n_tiles] = rs;
+                for (int q = 0; q < kRowsAhead; ++q)
+                    if (r0 + q < t.row1) nx[q] = ld_stream<f4>(vp + (uint64_t)(r0 + q - t.row0) * m.cols);
+            };
+            issue(r);
+            for (; r < t.row1; r += kRowsAhead) {
+                f4 cx[kRowsAhead];
+#pragma unroll
+                for (int q = 0; q < kRowsAhead; ++q) cx[q] = nx[q];
+                if (r + kRowsAhead < t.row1) issue(r + kRowsAhead);
+#pragma unroll
+                for (int q = 0; q < kRowsAhead; ++q) {
+                    if (r + q >= t.row1) break;
+                    const float x[4] = {cx[q].x, cx[q].y, cx[q].z, cx[q].w};
+                    const float rs = consume(std::true_type(), x);
+                    if (lane == 0) rp[(uint64_t)(r + q - t.row0) * m.n_tiles] = rs;
+                }
             }
-            row += (uint64_t)kRowsInFlight * m.cols; rp += (uint64_t)kRowsInFlight * m.n_tiles;
-        }
-        for (; r < t.row1; ++r) {
-            float x[4];
-            load_tile_row(row, t.vec, lane, t.ncols, x);
-            const float rs = consume(x);
-            if (lane == 0) *rp = rs;
-            row += m.cols; rp += m.n_tiles;
+        } else {
+            for (; r < t.row1; ++r) {
+                float x[4];
+                load_tile_row(row, t.vec, lane, t.ncols, x);
+                const float rs = consume(std::false_type(), x);
+                if (lane == 0) *rp = rs;
+                row += m.cols; rp += m.n_tiles;
+            }
         }
         float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
 #pragma unroll
@@ -805,7 +851,7 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
     }
     __syncthreads();
     uint32_t* out = hist_all + (uint64_t)m.block * 4 * kBins;
-    for (uint32_t i = threadIdx.x; i < kBins; i += 256)
+    for (uint32_t i = threadIdx.x; i < kBins1; i += 256)
         if (h[i]) atomicAdd(&out[i], h[i]);
 }
 
@@ -852,15 +898,22 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
     const MatRow* __restrict__ mats, uint32_t n_mats,
     const float* __restrict__ rvec, const float* __restrict__ cvec, const double* __restrict__ mu_all,
     const double* __restrict__ rec_all, const uint32_t* __restrict__ sel_prefix,
-    float* __restrict__ residpart, uint32_t* __restrict__ hist_all, float eps, bool want_F, bool want_C)
+    float* __restrict__ residpart, uint32_t* __restrict__ hist_all,
+    uint32_t* __restrict__ cand, uint32_t* __restrict__ cand_count, uint32_t* __restrict__ scan3,
+    float eps, bool want_F, bool want_C)
 {
     typedef GradIO<TT> IO;
-    __shared__ uint32_t h[4 * kBins];
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    for (uint32_t i = threadIdx.x; i < 4 * kBins; i += 256) h[i] = 0;
+    typedef typename IO::vec4 TV;
+    // LDS histograms for the first two distinct prefixes (lo and lo+1 of a quantile almost always share
+    // theirs); a third or fourth distinct prefix is rare and counts straight into global memory.
+    constexpr uint32_t NSLOT = 2;
+    __shared__ uint32_t h[NSLOT * kBins2];
+    const uint32_t lane = threadIdx.x & 63u, wave = scalar_wave_index();
+    for (uint32_t i = threadIdx.x; i < NSLOT * kBins2; i += 256) h[i] = 0;
     const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
     const MatRow& m = mats[t.mat];
     const Prefixes d = distinct_prefixes(sel_prefix, m.block);
+    uint32_t* hist_out = hist_all + (uint64_t)m.block * 4 * kBins;
     __syncthreads();
     if (t.valid) {
         const double mu = mu_all[t.mat];
@@ -879,59 +932,139 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
         const typename IO::elem* trow = theta + m.grad_start + first;
         const bool talign = (reinterpret_cast<uintptr_t>(trow) & IO::kAlignMask) == 0;   // cols % 4 == 0: same for all rows
         const float* rr = rvec + m.off_r + t.row0;
+        uint32_t* list = cand + m.cand_base + (uint64_t)(t.task - m.first_task) * m.cand_cap;
+        uint32_t n_cand = 0;                                  // uniform over the wavefront
         float res = 0.f, s2 = 0.f, cn = 0.f, cd = 0.f;
-        auto consume = [&](const float x[4], const float th[4], float ri) {
+        auto consume = [&](auto full, const float x[4], const float th[4], float ri) {
+            constexpr bool FULL = decltype(full)::value;     // every column of the lane is inside the tile
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (!ok[k]) continue;
+                const bool in = FULL || ok[k];
                 const uint32_t key = __builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu;
-                const uint32_t hi = key >> 20, bin = (key >> 9) & 0x7ffu;
-                count_match(h, d, kBins, hi, bin);
-                if (want_F) {
-                    const float d = x[k] - ri * cm[k];
-                    res = __builtin_fmaf(d, d, res);
-                    s2 = __builtin_fmaf(x[k], x[k], s2);
+                const uint32_t hi = key >> kShift1, bin = (key >> kShift2) & (kBins2 - 1);
+                bool hit = false;
+                if (in) {
+                    if (hi == d.pre[0]) { atomicAdd(&h[bin], 1u); hit = true; }
+                    else if (hi == d.pre[1]) { atomicAdd(&h[kBins2 + bin], 1u); hit = true; }
+                    else if (d.n > 2 && (hi == d.pre[2] || hi == d.pre[3])) {
+                        const uint32_t slot = hi == d.pre[2] ? 2u : 3u;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (d.slot_of[q] == slot) atomicAdd(&hist_out[q * kBins + bin], 1u);
+                        hit = true;
+                    }
                 }
-                if (want_C) {
-                    const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
-                    const float y = (p * inv_pbar - 1.0f) * th[k];
-                    cn = __builtin_fmaf(y, y, cn);
-                    cd = __builtin_fmaf(th[k], th[k], cd);
+                // candidates: the keys that carry a selected first digit, in the task's own list
+                const uint64_t hits = __builtin_amdgcn_ballot_w64(hit);
+                if (hits) {
+                    const uint32_t at = n_cand + __builtin_amdgcn_mbcnt_hi((uint32_t)(hits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hits, 0u));
+                    if (hit && at < m.cand_cap) list[at] = key;
+                    n_cand += (uint32_t)__builtin_popcountll(hits);
+                }
+                if (in) {
+                    if (want_F) {
+                        const float dd = x[k] - ri * cm[k];
+                        res = __builtin_fmaf(dd, dd, res);
+                        s2 = __builtin_fmaf(x[k], x[k], s2);
+                    }
+                    if (want_C) {
+                        const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                        const float y = (p * inv_pbar - 1.0f) * th[k];
+                        cn = __builtin_fmaf(y, y, cn);
+                        cd = __builtin_fmaf(th[k], th[k], cd);
+                    }
                 }
             }
         };
         uint32_t r = t.row0;
-        for (; r + kRowsInFlight <= t.row1; r += kRowsInFlight) {
-            float x[kRowsInFlight][4], th[kRowsInFlight][4];
+        if (t.vec && talign && t.ncols == kTileCols) {
+            const float* vp = row + 4 * lane;
+            const typename IO::elem* tp = trow + 4 * lane;
+            f4 nx[kRowsAhead]; TV nt[kRowsAhead]; float nr[kRowsAhead];
 #pragma unroll
-            for (int q = 0; q < (int)kRowsInFlight; ++q) {
-                load_tile_row(row + (uint64_t)q * m.cols, t.vec, lane, t.ncols, x[q]);
-                if (want_C) load_tile_theta<TT>(trow + (uint64_t)q * m.cols, t.vec, talign, lane, t.ncols, th[q]);
-                else th[q][0] = th[q][1] = th[q][2] = th[q][3] = 0.f;
+            for (int q = 0; q < kRowsAhead; ++q) { nx[q] = f4{0.f, 0.f, 0.f, 0.f}; nt[q] = TV{}; nr[q] = 0.f; }
+            auto issue = [&](uint32_t r0) {
+#pragma unroll
+                for (int q = 0; q < kRowsAhead; ++q)
+                    if (r0 + q < t.row1) {
+                        const uint64_t o = (uint64_t)(r0 + q - t.row0) * m.cols;
+                        nx[q] = ld_stream<f4>(vp + o);
+                        if (want_C) nt[q] = IO::loadv(tp + o);
+                        nr[q] = rr[r0 + q - t.row0];
+                    }
+            };
+            issue(r);
+            for (; r < t.row1; r += kRowsAhead) {
+                f4 cx[kRowsAhead]; TV ct[kRowsAhead]; float cr[kRowsAhead];
+#pragma unroll
+                for (int q = 0; q < kRowsAhead; ++q) { cx[q] = nx[q]; ct[q] = nt[q]; cr[q] = nr[q]; }
+                if (r + kRowsAhead < t.row1) issue(r + kRowsAhead);
+#pragma unroll
+                for (int q = 0; q < kRowsAhead; ++q) {
+                    if (r + q >= t.row1) break;
+                    const float x[4] = {cx[q].x, cx[q].y, cx[q].z, cx[q].w};
+                    float th[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (want_C) IO::unpack(ct[q], th);
+                    consume(std::true_type(), x, th, cr[q]);
+                }
             }
-#pragma unroll
-            for (int q = 0; q < (int)kRowsInFlight; ++q) consume(x[q], th[q], rr[q]);
-            row += (uint64_t)kRowsInFlight * m.cols; trow += (uint64_t)kRowsInFlight * m.cols; rr += kRowsInFlight;
-        }
-        for (; r < t.row1; ++r) {
-            float x[4], th[4] = {0.f, 0.f, 0.f, 0.f};
-            load_tile_row(row, t.vec, lane, t.ncols, x);
-            if (want_C) load_tile_theta<TT>(trow, t.vec, talign, lane, t.ncols, th);
-            consume(x, th, *rr);
-            row += m.cols; trow += m.cols; ++rr;
+        } else {
+            for (; r < t.row1; ++r) {
+                float x[4], th[4] = {0.f, 0.f, 0.f, 0.f};
+                load_tile_row(row, t.vec, lane, t.ncols, x);
+                if (want_C) load_tile_theta<TT>(trow, t.vec, talign, lane, t.ncols, th);
+                consume(std::false_type(), x, th, *rr);
+                row += m.cols; trow += m.cols; ++rr;
+            }
         }
         res = wave_sum(res); s2 = wave_sum(s2); cn = wave_sum(cn); cd = wave_sum(cd);
         if (lane == 0) {
             float* o = residpart + (uint64_t)t.task * 4;
             o[0] = res; o[1] = s2; o[2] = cn; o[3] = cd;
+            cand_count[t.task] = n_cand;
+            if (n_cand > m.cand_cap) scan3[m.block] = 1u;    // list too short: the block's last digit takes a third scan
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < kBins2; i += 256) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (d.slot_of[q] >= NSLOT) continue;
+            const uint32_t c = h[d.slot_of[q] * kBins2 + i];
+            if (c) atomicAdd(&hist_out[q * kBins + i], c);
+        }
+    }
+}
+
+// Third digit of the matrix blocks, counted on the candidate lists that the second tile pass wrote (a few
+// per cent of the coordinates).  Blocks flagged in scan3 are left to the third scan of v.
+__global__ __launch_bounds__(256) void k_cand_hist3(
+    const MatRow* __restrict__ mats, uint32_t n_mats, const uint32_t* __restrict__ cand,
+    const uint32_t* __restrict__ cand_count, const uint32_t* __restrict__ sel_prefix,
+    const uint32_t* __restrict__ scan3, uint32_t* __restrict__ hist_all)
+{
+    __shared__ uint32_t h[4 * kBins3];
+    const uint32_t lane = threadIdx.x & 63u, wave = scalar_wave_index();
+    const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
+    const MatRow& m = mats[t.mat];
+    if (scan3[m.block]) return;                              // the same for the whole workgroup (one block per quad)
+    for (uint32_t i = threadIdx.x; i < 4 * kBins3; i += 256) h[i] = 0;
+    const Prefixes d = distinct_prefixes(sel_prefix, m.block);
+    __syncthreads();
+    if (t.valid) {
+        const uint32_t n = min(cand_count[t.task], m.cand_cap);
+        const uint32_t* list = cand + m.cand_base + (uint64_t)(t.task - m.first_task) * m.cand_cap;
+        for (uint32_t i = lane; i < n; i += 64) {
+            const uint32_t key = list[i];
+            count_match(h, d, kBins3, key >> kShift2, key & (kBins3 - 1));
         }
     }
     __syncthreads();
     uint32_t* out = hist_all + (uint64_t)m.block * 4 * kBins;
-    for (uint32_t i = threadIdx.x; i < kBins; i += 256) {
+    for (uint32_t i = threadIdx.x; i < kBins3; i += 256) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint32_t c = h[d.slot_of[q] * kBins + i];
+            const uint32_t c = h[d.slot_of[q] * kBins3 + i];
             if (c) atomicAdd(&out[q * kBins + i], c);
         }
     }
@@ -1067,7 +1200,7 @@ struct Plan {
     std::vector<Slab> slabs;
     uint64_t off_slabs = 0, off_slabsums = 0;
     uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0,
-             off_psumpart = 0, off_veclist = 0;
+             off_psumpart = 0, off_veclist = 0, off_cand = 0, off_candcount = 0, off_scan3 = 0;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
     uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
              off_rec = 0, off_hist = 0, off_selp = 0, off_selr = 0, off_ostat = 0, total = 0;
@@ -1172,7 +1305,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     // Finalize walks blocks with a real matrix shape tile-wise and the rest chunk-wise.  A shape with a
     // single row or column is rank one by construction (F = 0 exactly) and stays on the chunk path.
     P.mats.clear(); P.n_tasks = 0; P.n_quads = 0; P.n_vec_chunks = 0;
-    uint64_t n_r = 0, n_c = 0, n_rowpart = 0, n_colpart = 0;
+    uint64_t n_r = 0, n_c = 0, n_rowpart = 0, n_colpart = 0, n_cand = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const baoc_block& b = blocks[i];
         if (b.rows < 2 || b.cols < 2) {
@@ -1186,10 +1319,17 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
         m.rows = b.rows; m.cols = b.cols;
         m.n_tiles = (b.cols + kTileCols - 1) / kTileCols; m.n_segs = (b.rows + kTileRows - 1) / kTileRows;
         m.off_r = n_r; m.off_c = n_c; m.off_rowpart = n_rowpart; m.off_colpart = n_colpart;
-        m.first_task = (uint32_t)P.n_tasks; m.first_quad = (uint32_t)P.n_quads; m.block = i; m.pad_ = 0;
+        m.first_task = (uint32_t)P.n_tasks; m.first_quad = (uint32_t)P.n_quads; m.block = i;
         n_r += b.rows; n_c += b.cols;
         n_rowpart += (uint64_t)b.rows * m.n_tiles; n_colpart += (uint64_t)m.n_segs * b.cols;
         const uint64_t tasks = (uint64_t)m.n_tiles * m.n_segs;
+        // one candidate list per task, an eighth of a tile long (the keys that share a selected first digit
+        // are a few per cent of a block unless its v is nearly constant; then the list overflows and the
+        // block takes the third scan)
+        const uint64_t tile_elems = (uint64_t)std::min(b.rows, kTileRows) * std::min(b.cols, kTileCols);
+        m.cand_cap = (uint32_t)align_up(std::max<uint64_t>(64, tile_elems / 8), 64);
+        m.cand_base = n_cand;
+        n_cand += tasks * m.cand_cap;
         P.n_tasks += tasks; P.n_quads += (tasks + 3) / 4;
         if (P.n_tasks > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
         P.mats.push_back(m);
@@ -1218,6 +1358,9 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_veclist = o;  o = align_up(o + P.n_vec_chunks * 4, 256);
     P.off_slabs = o;    o = align_up(o + P.slabs.size() * sizeof(Slab), 256);
     P.off_slabsums = o; o = align_up(o + P.slabs.size() * kNumSums * 8, 256);
+    P.off_candcount = o; o = align_up(o + P.n_tasks * 4, 256);
+    P.off_scan3 = o;    o = align_up(o + (uint64_t)n * 4, 256);
+    P.off_cand = o;     o = align_up(o + n_cand * 4, 256);
     P.total = o;
     return BAOC_OK;
 }
@@ -1409,12 +1552,18 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
     const uint64_t hist_words = (uint64_t)N * 4 * kBins;
     const uint32_t fill_grid = (uint32_t)std::min<uint64_t>((hist_words + 255) / 256, 4096);
 
+    uint32_t* cand = reinterpret_cast<uint32_t*>(h->ws + P.off_cand);
+    uint32_t* cand_count = reinterpret_cast<uint32_t*>(h->ws + P.off_candcount);
+    uint32_t* scan3 = reinterpret_cast<uint32_t*>(h->ws + P.off_scan3);
+    const uint32_t* no_list = nullptr;
+    const uint32_t* no_flags = nullptr;
+
     // pass 1 over v: first digit everywhere; row/column sums and the sum of p on the way
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
     if (n_quads)
         hipLaunchKernelGGL(k_tile_pass1, dim3(n_quads), dim3(256), 0, st, v, mats, n_mats, rowpart, colpart, psumpart, hist, epsf, want_C);
     if (n_vec) {
-        hipLaunchKernelGGL(k_hist<1>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist);
+        hipLaunchKernelGGL(k_hist<1>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist, rows, no_flags);
         if (want_C) {
             if (th32) hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 1>), dim3(n_vec), dim3(256), 0, st, v, th_f, ch, vec_list, rows, rec, part, epsf);
             else hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 1>), dim3(n_vec), dim3(256), 0, st, v, th_h, ch, vec_list, rows, rec, part, epsf);
@@ -1423,29 +1572,33 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
     }
     if (n_quads)
         hipLaunchKernelGGL(k_tile_finish1, dim3(n_mats), dim3(256), 0, st, mats, rowpart, colpart, psumpart, rvec, cvec, mu, rec);
-    hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
+    hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat, scan3);
 
-    // pass 2 over v (and theta): second digit; rank-1 residual and distortion on the way
+    // pass 2 over v (and theta): second digit; rank-1 residual and distortion on the way; matrix blocks
+    // also set aside the keys that carry a selected first digit
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
     if (n_quads) {
-        if (th32) hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_F32>, dim3(n_quads), dim3(256), 0, st, v, th_f, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, epsf, want_F, want_C);
-        else hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_BF16>, dim3(n_quads), dim3(256), 0, st, v, th_h, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, epsf, want_F, want_C);
+        if (th32) hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_F32>, dim3(n_quads), dim3(256), 0, st, v, th_f, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, cand, cand_count, scan3, epsf, want_F, want_C);
+        else hipLaunchKernelGGL(k_tile_pass2<BAOC_GRAD_BF16>, dim3(n_quads), dim3(256), 0, st, v, th_h, mats, n_mats, rvec, cvec, mu, rec, selp, residpart, hist, cand, cand_count, scan3, epsf, want_F, want_C);
         hipLaunchKernelGGL(k_tile_finish2, dim3(n_mats), dim3(256), 0, st, mats, residpart, rec);
     }
     if (n_vec) {
-        hipLaunchKernelGGL(k_hist<2>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist);
+        hipLaunchKernelGGL(k_hist<2>, dim3(std::min(n_vec, kHistGrid)), dim3(256), 0, st, v, ch, vec_list, n_vec, selp, hist, rows, no_flags);
         if (want_C) {
             if (th32) hipLaunchKernelGGL((k_distortion<BAOC_GRAD_F32, 2>), dim3(n_vec), dim3(256), 0, st, v, th_f, ch, vec_list, rows, rec, part, epsf);
             else hipLaunchKernelGGL((k_distortion<BAOC_GRAD_BF16, 2>), dim3(n_vec), dim3(256), 0, st, v, th_h, ch, vec_list, rows, rec, part, epsf);
             hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 2u, (uint32_t)R_CNUM);
         }
     }
-    hipLaunchKernelGGL(k_pick<2>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
+    hipLaunchKernelGGL(k_pick<2>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat, scan3);
 
-    // pass 3 over v: last digit, chunk-wise for every block
+    // last digit: on the candidate lists of the matrix blocks; by a third scan of v for the blocks walked
+    // chunk-wise and for matrix blocks whose lists overflowed (scan3 flags, skipped a block at a time otherwise)
     hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid), dim3(256), 0, st, hist, hist_words, 0u);
-    hipLaunchKernelGGL(k_hist<3>, dim3(std::min(nch, kHistGrid)), dim3(256), 0, st, v, ch, static_cast<const uint32_t*>(nullptr), nch, selp, hist);
-    hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat);
+    if (n_quads)
+        hipLaunchKernelGGL(k_cand_hist3, dim3(n_quads), dim3(256), 0, st, mats, n_mats, cand, cand_count, selp, scan3, hist);
+    hipLaunchKernelGGL(k_hist<3>, dim3(std::min(nch, kHistGrid)), dim3(256), 0, st, v, ch, no_list, nch, selp, hist, rows, static_cast<const uint32_t*>(scan3));
+    hipLaunchKernelGGL(k_pick<3>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat, scan3);
 
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h->h_rec.data(), h->ws + P.off_rec, h->h_rec.size() * 8, hipMemcpyDeviceToHost, st);

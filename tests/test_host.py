@@ -51,7 +51,7 @@ def test_workspace_size_tracks_the_state_bytes():
         w = W.make(name)
         n = ws(w.blocks, grad_dtype=1 if w.grad_dtype == "bf16" else 0)
         per = 10 if w.grad_dtype == "bf16" else 12
-        assert per * w.numel <= n <= per * w.numel * 1.02 + (1 << 20) + 40_000 * len(w.blocks)
+        assert per * w.numel <= n <= (per + 0.5) * w.numel * 1.02 + (1 << 20) + 40_000 * len(w.blocks)   # + candidate lists: 4 bytes per 8 coordinates
 
 
 def test_layout_validation():
