@@ -855,15 +855,20 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
         if (h[i]) atomicAdd(&out[i], h[i]);
 }
 
-// r_i, c_j (fp32 for pass 2), mu (fp64) and the block's sum of p from the pass-1 partial sums.
+// r_i, c_j (fp32 for pass 2) and, per slice, the sums behind mu and the block's sum of p, from the pass-1
+// partial sums.  A matrix block is cut into kFinSlices slices of rows, of columns and of tasks (grid.y).
+constexpr uint32_t kFinSlices = 32;
+
 __global__ __launch_bounds__(256) void k_tile_finish1(const MatRow* __restrict__ mats, const float* __restrict__ rowpart,
                                                       const float* __restrict__ colpart, const float* __restrict__ psumpart,
                                                       float* __restrict__ rvec, float* __restrict__ cvec,
-                                                      double* __restrict__ mu_out, double* __restrict__ rec_all)
+                                                      double* __restrict__ finpart)
 {
     const MatRow m = mats[blockIdx.x];
+    const uint32_t y = blockIdx.y;
     double local = 0.0, lp = 0.0;
-    for (uint32_t i = threadIdx.x; i < m.rows; i += 256) {
+    const uint32_t rper = (m.rows + kFinSlices - 1) / kFinSlices, i1 = min(m.rows, (y + 1) * rper);
+    for (uint32_t i = y * rper + threadIdx.x; i < i1; i += 256) {
         const float* rp = rowpart + m.off_rowpart + (uint64_t)i * m.n_tiles;
         double s = 0.0;
         for (uint32_t t = 0; t < m.n_tiles; ++t) s += (double)rp[t];
@@ -871,14 +876,15 @@ __global__ __launch_bounds__(256) void k_tile_finish1(const MatRow* __restrict__
         rvec[m.off_r + i] = (float)r;
         local += r;
     }
-    for (uint32_t j = threadIdx.x; j < m.cols; j += 256) {
+    const uint32_t cper = (m.cols + kFinSlices - 1) / kFinSlices, j1 = min(m.cols, (y + 1) * cper);
+    for (uint32_t j = y * cper + threadIdx.x; j < j1; j += 256) {
         const float* cp = colpart + m.off_colpart + j;
         double s = 0.0;
         for (uint32_t g = 0; g < m.n_segs; ++g) s += (double)cp[(uint64_t)g * m.cols];
         cvec[m.off_c + j] = (float)(s / (double)m.rows);
     }
-    const uint32_t n_tasks = m.n_tiles * m.n_segs;
-    for (uint32_t i = threadIdx.x; i < n_tasks; i += 256) lp += (double)psumpart[m.first_task + i];
+    const uint32_t n_tasks = m.n_tiles * m.n_segs, tper = (n_tasks + kFinSlices - 1) / kFinSlices, k1 = min(n_tasks, (y + 1) * tper);
+    for (uint32_t i = y * tper + threadIdx.x; i < k1; i += 256) lp += (double)psumpart[m.first_task + i];
     __shared__ double sh[256], sp[256];
     sh[threadIdx.x] = local; sp[threadIdx.x] = lp;
     __syncthreads();
@@ -887,9 +893,22 @@ __global__ __launch_bounds__(256) void k_tile_finish1(const MatRow* __restrict__
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        mu_out[blockIdx.x] = sh[0] / (double)m.rows;
-        rec_all[(uint64_t)m.block * kRecDoubles + R_PSUM] = sp[0];
+        double* o = finpart + ((uint64_t)blockIdx.x * kFinSlices + y) * 2;
+        o[0] = sh[0]; o[1] = sp[0];
     }
+}
+
+// mu (fp64) and the block's sum of p: the slices of k_tile_finish1 added in a fixed order.
+__global__ __launch_bounds__(64) void k_tile_finish1_sum(const MatRow* __restrict__ mats, const double* __restrict__ finpart,
+                                                         double* __restrict__ mu_out, double* __restrict__ rec_all)
+{
+    if (threadIdx.x != 0) return;
+    const MatRow& m = mats[blockIdx.x];
+    const double* in = finpart + (uint64_t)blockIdx.x * kFinSlices * 2;
+    double a = 0.0, p = 0.0;
+    for (uint32_t y = 0; y < kFinSlices; ++y) { a += in[2 * y]; p += in[2 * y + 1]; }
+    mu_out[blockIdx.x] = a / (double)m.rows;
+    rec_all[(uint64_t)m.block * kRecDoubles + R_PSUM] = p;
 }
 
 template <int TT>
@@ -1200,7 +1219,7 @@ struct Plan {
     std::vector<Slab> slabs;
     uint64_t off_slabs = 0, off_slabsums = 0;
     uint64_t off_mats = 0, off_rvec = 0, off_cvec = 0, off_rowpart = 0, off_colpart = 0, off_residpart = 0, off_mu = 0,
-             off_psumpart = 0, off_veclist = 0, off_cand = 0, off_candcount = 0, off_scan3 = 0;
+             off_psumpart = 0, off_veclist = 0, off_cand = 0, off_candcount = 0, off_scan3 = 0, off_finpart = 0;
     uint64_t padded = 0;          // coordinates in m / v / g_prev
     uint64_t off_m = 0, off_v = 0, off_gp = 0, off_partials = 0, off_chunks = 0, off_rows = 0,
              off_rec = 0, off_hist = 0, off_selp = 0, off_selr = 0, off_ostat = 0, total = 0;
@@ -1360,6 +1379,7 @@ static int make_plan(const baoc_block* blocks, uint32_t n, const baoc_profile_pa
     P.off_slabsums = o; o = align_up(o + P.slabs.size() * kNumSums * 8, 256);
     P.off_candcount = o; o = align_up(o + P.n_tasks * 4, 256);
     P.off_scan3 = o;    o = align_up(o + (uint64_t)n * 4, 256);
+    P.off_finpart = o;  o = align_up(o + P.mats.size() * kFinSlices * 2 * 8, 256);
     P.off_cand = o;     o = align_up(o + n_cand * 4, 256);
     P.total = o;
     return BAOC_OK;
@@ -1570,8 +1590,11 @@ extern "C" int baoc_profile_finalize(baoc_profiler* h, const baoc_config* config
             hipLaunchKernelGGL(k_reduce_partials, dim3(N), dim3(256), 0, st, part, rows, rec, 1u, (uint32_t)R_PSUM);
         }
     }
-    if (n_quads)
-        hipLaunchKernelGGL(k_tile_finish1, dim3(n_mats), dim3(256), 0, st, mats, rowpart, colpart, psumpart, rvec, cvec, mu, rec);
+    if (n_quads) {
+        double* finpart = reinterpret_cast<double*>(h->ws + P.off_finpart);
+        hipLaunchKernelGGL(k_tile_finish1, dim3(n_mats, kFinSlices), dim3(256), 0, st, mats, rowpart, colpart, psumpart, rvec, cvec, finpart);
+        hipLaunchKernelGGL(k_tile_finish1_sum, dim3(n_mats), dim3(64), 0, st, mats, finpart, mu, rec);
+    }
     hipLaunchKernelGGL(k_pick<1>, dim3(N * 4), dim3(64), 0, st, hist, rows, selp, selr, ostat, scan3);
 
     // pass 2 over v (and theta): second digit; rank-1 residual and distortion on the way; matrix blocks
