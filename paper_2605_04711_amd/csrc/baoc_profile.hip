@@ -129,6 +129,18 @@ __device__ __forceinline__ float direction(float m, float v, float eps_u)
     return m * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v) + eps_u);
 }
 
+// Preconditioner of Eq. 6, p = 1 / (sqrt(v) + eps), with one transcendental instead of two where eps is small
+// against sqrt(v): with r = 1/sqrt(v), p = r / (1 + eps r) = r (1 - eps r) up to (eps r)^2 < 1e-6.  Elsewhere
+// (v tiny, zero, sub-normal or NaN) the plain form.
+__device__ __forceinline__ float preconditioner(float v, float eps)
+{
+    const float r = __builtin_amdgcn_rsqf(v);
+    const float er = eps * r;
+    float p = __builtin_fmaf(-er, r, r);
+    if (!(er < 1e-3f)) p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v) + eps);
+    return p;
+}
+
 // Every array is touched exactly once per pass: load and store with the nontemporal hint so the
 // stream does not displace anything in L2 / MALL on its way through.
 template <typename T> __device__ __forceinline__ T ld_stream(const void* p)
@@ -802,7 +814,7 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
                 cs[k] += (double)x[k];
                 if (FULL || ok[k]) {
                     atomicAdd(&h[(__builtin_bit_cast(uint32_t, x[k]) & 0x7fffffffu) >> kShift1], 1u);
-                    if (want_p) prow += __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                    if (want_p) prow += preconditioner(x[k], eps);
                 }
             }
             psum += (double)prow;
@@ -987,7 +999,7 @@ __global__ __launch_bounds__(256) void k_tile_pass2(
                         s2 = __builtin_fmaf(x[k], x[k], s2);
                     }
                     if (want_C) {
-                        const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(x[k]) + eps);
+                        const float p = preconditioner(x[k], eps);
                         const float y = (p * inv_pbar - 1.0f) * th[k];
                         cn = __builtin_fmaf(y, y, cn);
                         cd = __builtin_fmaf(th[k], th[k], cd);
@@ -1152,7 +1164,7 @@ __global__ __launch_bounds__(256) void k_distortion(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (e + j < ck.count) {                          // padding coordinates are not part of the block
-                const float p = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v[j]) + eps);
+                const float p = preconditioner(v[j], eps);
                 if (PASS == 1) a0 += p;
                 else {
                     const float x = (p * inv_pbar - 1.0f) * th[j];
