@@ -42,9 +42,9 @@ def parse():
     ap.add_argument("--sample-ratio", type=float, default=0.0,
                     help="sparse coordinate sampling (Sec. 3.1): gather g[Omega] with this ratio before every step and profile "
                          "the compact buffer; prints its own JSON line (not the headline metric)")
-    ap.add_argument("--memory-probe", action="store_true",
-                    help="instead of the benchmark: pure streams with the step kernel's traffic mix (no arithmetic), read-only and "
-                         "write-only, at several residencies -- what this HBM system delivers; prints its own JSON line")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the steady-state step figures of the gpt_1p3b and unet layouts and the pure-stream ceiling "
+                         "that the default run appends to its line")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "k_step_pmc_traffic.txt"))
     return ap.parse_args()
 
@@ -146,40 +146,63 @@ def sampled_windows(a, w, ring, theta, params, mem, tc, b_mem, cap):
                          "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": g_avg, "launches": len(g_ms)}}
 
 
-def memory_probe(coordinates, dev):
-    """Pure streams of the bf16 step kernel's bytes (22 per coordinate: 4 reads, 3 writes), of reads and of writes alone."""
+def practical_ceiling(w, g, dev):
+    """What this HBM system delivers for the step kernel's byte mix with no arithmetic: a pure stream of
+    22 bytes per coordinate (4 reads, 3 writes) in its best launch shape, median of 5 launches.  bf16 gradients only."""
     import torch
     from synth import device
+    if w.grad_dtype != "bf16":
+        return None
     L = device.probe_lib()
-    n = coordinates // 4096 * 4096
+    n = min(w.numel, g.numel()) // 512 * 512
     m = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros_like(m)
-    gp = torch.zeros(n, dtype=torch.bfloat16, device=dev); g = torch.zeros_like(gp)
-    sink = torch.zeros(256, dtype=torch.float32, device=dev)
+    gp = torch.zeros(n, dtype=torch.bfloat16, device=dev)
     st = torch.cuda.current_stream(dev).cuda_stream
 
-    def run(kind, waves, groups, resident):
-        lds = 0 if not resident else 160 * 1024 // resident // 2048 * 2048        # unused LDS that limits the residency
-        def launch():
-            rc = L.synth_mem_probe(kind, waves, groups, lds, n, m.data_ptr(), v.data_ptr(), gp.data_ptr(), g.data_ptr(), sink.data_ptr(), st)
-            if rc:
-                raise RuntimeError(f"synth_mem_probe: {rc}")
-        launch(); torch.cuda.synchronize()
-        ms = []
-        for _ in range(5):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); launch(); e1.record(); e1.synchronize()
-            ms.append(e0.elapsed_time(e1))
-        t = sorted(ms)[2]
-        nbytes = (22 if kind == 0 else 4) * n
-        return {"stream": ("mix 4r3w", "read", "write")[kind], "waves_per_workgroup": waves, "groups_per_wave": groups,
-                "resident_workgroups": resident or "unlimited", "waves_per_cu": (resident * waves) if resident else "max",
-                "ms": round(t, 3), "GB/s": round(nbytes / t / 1e6)}
+    def launch():
+        rc = L.synth_mix_stream(n, m.data_ptr(), v.data_ptr(), gp.data_ptr(), g.data_ptr(), st)
+        if rc:
+            raise RuntimeError(f"synth_mix_stream: {rc}")
+    launch(); torch.cuda.synchronize()
+    ms = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); launch(); e1.record(); e1.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    t = sorted(ms)[2]
+    gbs = 22 * n / t / 1e6
+    return {"GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "ms": t, "coordinates": n,
+            "what": "pure stream of the step kernel's 22 B/coordinate (4 reads, 3 writes, no arithmetic): single-wavefront "
+                    "workgroups of 2 groups, 4 resident per CU; median of 5 launches"}
 
-    rows = [run(1, 4, 1, 0), run(1, 4, 2, 0), run(2, 4, 1, 0), run(2, 4, 2, 0)]
-    for waves, groups, resident in [(4, 1, 0), (4, 2, 0), (4, 2, 4), (4, 2, 3), (2, 2, 8), (2, 2, 4), (2, 2, 3), (1, 2, 16), (1, 2, 10),
-                                    (1, 2, 6), (1, 2, 4), (1, 4, 8), (1, 4, 4), (1, 4, 3), (4, 1, 0)]:
-        rows.append(run(0, waves, groups, resident))
-    return {"metric": "memory-system probe", "unit": "GB/s", "peak": HBM_PEAK_GBS, "coordinates": n, "rows": rows}
+
+def secondary_steps(names, a, dev):
+    """Steady-state step launches of further layouts (begin, the first step, then `launches` timed steps each)."""
+    import torch
+    from paper_2605_04711_amd import binding
+    from synth import device, workloads as W
+    out = []
+    for name in names:
+        w = W.make(name, seed=a.seed)
+        params = binding.default_profile_params(grad_dtype=1 if w.grad_dtype == "bf16" else 0)
+        ring = [device.fill(w, device.new_buffer(w, dev), a.seed, t + 1) for t in range(2)]
+        prof = binding.Profiler(w.blocks, params, device=dev)
+        launches = 8
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches + 2)]
+        for t in range(launches + 2):                                   # launch 0: first-step kernel, launch 1: warm-up
+            ev[t][0].record(); prof.step(ring[t % 2]); ev[t][1].record()
+        torch.cuda.synchronize()
+        ms = [e0.elapsed_time(e1) for e0, e1 in ev][2:]
+        prof.close()
+        del prof, ring
+        avg = sum(ms) / len(ms)
+        bpe = BYTES_PER_ELEM[w.grad_dtype]
+        out.append({"workload": name, "blocks": len(w.blocks), "coordinates": w.numel, "grad_dtype": w.grad_dtype,
+                    "kernel": "k_step (steady state)", "avg_launch_ms": avg, "min_launch_ms": min(ms), "launches": launches,
+                    "algorithmic_bytes_per_launch": bpe * w.numel, "achieved": bpe * w.numel / avg / 1e6, "unit": "GB/s",
+                    "frac": bpe * w.numel / avg / 1e6 / HBM_PEAK_GBS, "step_only_elements_per_s": w.numel / (avg * 1e-3)})
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -198,9 +221,6 @@ def main():
         sys.exit(2)
     B.load_library(); device.lib()
     dev = torch.device("cuda:0")
-    if a.memory_probe:
-        print(json.dumps(memory_probe(W.make(a.workload, seed=a.seed).numel, dev)))
-        return
     w = W.make(a.workload, seed=a.seed)
     K = a.steps or w.T
     D = w.numel
@@ -289,6 +309,15 @@ def main():
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ring, a.seed, params)
+    if not a.no_secondary and a.workload == "llama7b":
+        # after the headline window: the pure-stream ceiling of this byte mix, and the steady-state step of the
+        # two fp32 layouts the bandwidth target also names (1.3B-shaped decoder, UNet-shaped)
+        del theta
+        torch.cuda.empty_cache()
+        out["roofline"]["practical_ceiling"] = practical_ceiling(w, ring[0], dev)
+        del ring
+        torch.cuda.empty_cache()
+        out["secondary"] = secondary_steps(["gpt_1p3b", "unet"], a, dev)
     print(json.dumps(out))
 
 

@@ -133,8 +133,9 @@ void baoc_risk_params_default(baoc_risk_params* p);
 
 /* Device workspace needed for this block layout: the fp32 states m, v (Eq. 3),
  * the previous gradient (Eq. 5) in the gradient's dtype, per-workgroup partial
- * sums, tables and the quantile scratch; roughly 12 (fp32 gradients) or 10
- * (bf16) bytes per profiled coordinate.  blocks: HOST array of n_blocks. */
+ * sums, tables and the quantile scratch (for matrix blocks: candidate lists of
+ * 4 bytes per 8 coordinates); roughly 12.7 (fp32 gradients) or 10.6 (bf16) bytes
+ * per profiled coordinate.  blocks: HOST array of n_blocks. */
 int baoc_profile_workspace_bytes(const baoc_block* blocks, uint32_t n_blocks,
                                  const baoc_profile_params* params, uint64_t* out_bytes);
 
@@ -156,7 +157,7 @@ int baoc_profile_begin(const baoc_block* blocks, uint32_t n_blocks,
  * handles begun this way on one GPU share it: only one may be alive per GPU at a time (a second begin
  * before baoc_profile_end returns STATE), and work still queued on a stream for an ended handle races
  * with the next one.  Errors: WORKSPACE when baoc_profile_workspace_bytes of the layout exceeds
- * BAOC_STATIC_WORKSPACE_BYTES (about 13 M coordinates with bf16 gradients, 11 M with fp32);
+ * BAOC_STATIC_WORKSPACE_BYTES (about 12 M coordinates with bf16 gradients, 10 M with fp32);
  * UNSUPPORTED for a device ordinal above 63; otherwise as baoc_profile_begin. */
 #define BAOC_STATIC_WORKSPACE_BYTES (128ull << 20)
 int baoc_profile_begin_static(const baoc_block* blocks, uint32_t n_blocks,
@@ -256,7 +257,7 @@ int baoc_sample_end(baoc_sampler* s);
  * n_blocks entries; out_objective / out_mem / out_time may be NULL and receive
  * sum(phi)/1e9, sum(mem) and sum(tau)/1e6 of the answer.
  * Errors: INVALID (null, zero sizes, negative memory, NaN budget),
- * INFEASIBLE, LIMIT. */
+ * INFEASIBLE, LIMIT (state limit of the search, or host memory exhausted). */
 int baoc_allocate(const double* risk, const int64_t* mem_cost_bytes, const double* time_cost,
                   uint32_t n_blocks, uint32_t n_configs,
                   int64_t mem_budget_bytes, double time_budget_sum,
@@ -274,8 +275,8 @@ int baoc_allocate(const double* risk, const int64_t* mem_cost_bytes, const doubl
  * merged again.  out_block_of_unit (n_units) receives ascending block ids from 0; a
  * block's statistics are the parameter-weighted mean of its units.  All pointers HOST;
  * out_n_blocks and out_tau may be NULL.  Errors: INVALID (null, zero sizes, non-finite z,
- * negative weights, alpha outside [0,1]), UNSUPPORTED (more than 32,768 units: tau is a
- * quantile over all unit pairs, so time and memory grow with n_units^2). */
+ * negative weights, alpha outside [0,1]), UNSUPPORTED (more than 32,768 units, or not enough host memory
+ * for the pair table: tau is a quantile over all unit pairs, so time and memory grow with n_units^2). */
 int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
                    const double* weights, double alpha,
                    uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau);

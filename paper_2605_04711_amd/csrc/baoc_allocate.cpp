@@ -26,6 +26,7 @@
 #include <cstdint>
 #include <cstring>
 #include <limits>
+#include <new>
 #include <vector>
 
 #include "baoc_internal.h"
@@ -385,10 +386,10 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
 
 extern "C" void baoc_allocate_set_node_limit(uint64_t max_nodes) { g_node_limit = max_nodes; }
 
-extern "C" int baoc_allocate(const double* risk, const int64_t* mem, const double* time_cost,
-                             uint32_t N, uint32_t K, int64_t mem_budget, double time_budget_sum,
-                             const uint8_t* forbidden,
-                             uint32_t* out_choice, double* out_objective, int64_t* out_mem, double* out_time)
+static int allocate(const double* risk, const int64_t* mem, const double* time_cost,
+                    uint32_t N, uint32_t K, int64_t mem_budget, double time_budget_sum,
+                    const uint8_t* forbidden,
+                    uint32_t* out_choice, double* out_objective, int64_t* out_mem, double* out_time)
 {
     if (!risk || !mem || !time_cost || !out_choice || N == 0 || K == 0) return BAOC_ERR_INVALID;
     if (time_budget_sum != time_budget_sum) return BAOC_ERR_INVALID;
@@ -434,4 +435,18 @@ extern "C" int baoc_allocate(const double* risk, const int64_t* mem, const doubl
     if (out_mem) *out_mem = W;
     if (out_time) *out_time = (double)T / kTauScale;
     return BAOC_OK;
+}
+
+// No exception crosses the C boundary: running out of host memory for the state lists is the same event as
+// reaching the state limit.
+extern "C" int baoc_allocate(const double* risk, const int64_t* mem, const double* time_cost,
+                             uint32_t N, uint32_t K, int64_t mem_budget, double time_budget_sum,
+                             const uint8_t* forbidden,
+                             uint32_t* out_choice, double* out_objective, int64_t* out_mem, double* out_time)
+{
+    try {
+        return allocate(risk, mem, time_cost, N, K, mem_budget, time_budget_sum, forbidden, out_choice, out_objective, out_mem, out_time);
+    } catch (const std::bad_alloc&) {
+        return BAOC_ERR_LIMIT;
+    }
 }

@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "baoc.h"
@@ -97,9 +98,9 @@ void split(const Ctx& c, const std::vector<Units>& temp, size_t lo, size_t hi, d
 
 }  // namespace
 
-extern "C" int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
-                              const double* weights, double alpha,
-                              uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau)
+static int partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
+                     const double* weights, double alpha,
+                     uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau)
 {
     if (!unit_numel || !z || !out_block_of_unit || n_units == 0 || n_stats == 0) return BAOC_ERR_INVALID;
     if (!(alpha >= 0.0) || !(alpha <= 1.0)) return BAOC_ERR_INVALID;
@@ -164,4 +165,17 @@ extern "C" int baoc_partition(const uint64_t* unit_numel, const double* z, uint3
     if (out_n_blocks) *out_n_blocks = (uint32_t)fin.size();
     if (out_tau) *out_tau = tau;
     return BAOC_OK;
+}
+
+// No exception crosses the C boundary: running out of host memory (the pair table of a call near the unit
+// limit takes about 4 GB) is reported like a size this build does not handle.
+extern "C" int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units, uint32_t n_stats,
+                              const double* weights, double alpha,
+                              uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau)
+{
+    try {
+        return partition(unit_numel, z, n_units, n_stats, weights, alpha, out_block_of_unit, out_n_blocks, out_tau);
+    } catch (const std::bad_alloc&) {
+        return BAOC_ERR_UNSUPPORTED;
+    }
 }

@@ -9,11 +9,11 @@
 //   Eq. 5  <g_t, g_{t-1}>, |g_t|^2, |m|^2, |v|_1
 //   Eq. 8  update directions u = m/(sqrt(v)+eps_u) from the fp32 state and from
 //          the state after a bf16 or a block-wise absmax 8-bit round trip.
-// Work is cut into chunks that never straddle a parameter block; one workgroup
-// (4 wavefronts) owns a chunk, one wavefront owns a 256-coordinate quantisation
-// group at a time (4 coordinates per lane), so the group's absmax is a DPP
-// reduction inside the wavefront.  Sums go wavefront (DPP) -> workgroup (LDS)
-// -> one partial row per chunk -> per parameter block in fp64 (second kernel).
+// Work is cut into chunks that never straddle a parameter block; the step kernel cuts a chunk into
+// slices, one workgroup (1, 2 or 4 wavefronts, a launch-shape parameter) and one partial row each.  A
+// wavefront owns whole 256-coordinate quantisation groups (4 coordinates per lane, one or two groups
+// next to each other), so a group's absmax is a DPP reduction inside the wavefront.  Sums go wavefront
+// (DPP) -> workgroup (LDS) -> one partial row per workgroup -> per parameter block in fp64 (second kernel).
 // No float atomics anywhere: two runs give identical bits.
 #include <hip/hip_runtime.h>
 

@@ -24,14 +24,13 @@ def build_probe():
 
 
 def probe_lib():
-    """The memory-system probe (csrc/memprobe.hip): pure streams with the step kernel's traffic mix."""
+    """The pure-stream probe (csrc/memprobe.hip): the step kernel's traffic mix with no arithmetic."""
     global _probe
     if _probe is None:
         if not os.path.exists(PROBE_LIB):
             build_probe()
         _probe = C.CDLL(PROBE_LIB)
-        _probe.synth_mem_probe.argtypes = [C.c_int, C.c_int, C.c_int, C.c_uint32, C.c_uint64,
-                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _probe.synth_mix_stream.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     return _probe
 
 
