@@ -82,6 +82,9 @@ def lib():
         L.orc_sample_count.argtypes = [u64, f64]
         L.orc_sample_indices.restype = None
         L.orc_sample_indices.argtypes = [u64, u64, u64, u32, vp]
+        L.orc_sample_matrix_shape.argtypes = [u32, u32, f64, C.POINTER(u32), C.POINTER(u32)]
+        L.orc_sample_indices_matrix.restype = None
+        L.orc_sample_indices_matrix.argtypes = [u32, u32, u32, u32, u64, u32, vp]
         L.orc_bf16_round.restype = f32
         L.orc_bf16_round.argtypes = [f32]
         L.orc_q8_code.restype = f32
@@ -212,6 +215,26 @@ def sample_indices(d, s, seed, block):
     out = np.zeros(k, np.uint64)
     lib().orc_sample_indices(int(d), k, int(seed), int(block), out.ctypes.data)
     return out
+
+
+def sample_matrix_shape(rows, cols, s):
+    """(r, c) of the sampled sub-matrix of a rows x cols block, or None when the sample has no matrix form."""
+    r, c = C.c_uint32(), C.c_uint32()
+    if not lib().orc_sample_matrix_shape(int(rows), int(cols), float(s), C.byref(r), C.byref(c)):
+        return None
+    return r.value, c.value
+
+
+def sample_indices_block(numel, rows, cols, s, seed, block):
+    """Omega of one block as positions inside the block, and the compact block's (rows, cols): the product
+    form for matrix blocks (sub-matrix, row-major), the flat stratified draw otherwise ((0, 0))."""
+    shape = sample_matrix_shape(rows, cols, s) if rows and cols else None
+    if shape is None:
+        return sample_indices(numel, s, seed, block), (0, 0)
+    r, c = shape
+    out = np.zeros(r * c, np.uint64)
+    lib().orc_sample_indices_matrix(int(rows), int(cols), r, c, int(seed), int(block), out.ctypes.data)
+    return out, (r, c)
 
 
 def phi(stats, cfg, preferred=False, rp=None):

@@ -246,6 +246,47 @@ void orc_sample_indices(uint64_t d, uint64_t k, uint64_t seed, uint32_t block, u
     }
 }
 
+/* Matrix form of the sampled coordinates.  Eq. 7 is stated on "the matrix form of the sampled gradients"
+   while Sec. 3.1 fixes only the count.  Reading: for a rows x cols block Omega is a product set of r rows
+   and c columns, so that the sampled coordinates are a sub-matrix (row-major in the compact buffer):
+   r = round(rows sqrt(s)) within [1, rows], c = the least count with r c >= ceil(s d), at most cols.
+   Returns 1 and the shape when both r and c are at least 2; 0 when the block has no matrix shape or the
+   sample is too thin for one (then the flat draw above applies and F = 0). */
+int orc_sample_matrix_shape(uint32_t rows, uint32_t cols, double s, uint32_t *r_out, uint32_t *c_out)
+{
+    if (rows < 2 || cols < 2) return 0;
+    uint64_t target = orc_sample_count((uint64_t)rows * cols, s);
+    double rr = floor((double)rows * sqrt(s) + 0.5);
+    if (!(rr >= 1.0)) rr = 1.0;
+    if (rr > (double)rows) rr = (double)rows;
+    uint64_t r = (uint64_t)rr, c = (target + r - 1) / r;
+    if (c > cols) c = cols;
+    if (r < 2 || c < 2) return 0;
+    *r_out = (uint32_t)r; *c_out = (uint32_t)c;
+    return 1;
+}
+
+/* The r rows and c columns are drawn like the coordinates of the flat draw: one out of each of r (c) equal
+   strata of the row (column) range, by a 64-bit mix of (seed, block, axis, stratum).  out[a c + b] is the
+   position of (row a, column b) inside the block, ascending. */
+void orc_sample_indices_matrix(uint32_t rows, uint32_t cols, uint32_t r, uint32_t c, uint64_t seed, uint32_t block,
+                               uint64_t *out)
+{
+    const uint64_t key = mix64(mix64(seed) + block);
+    const uint64_t key_r = mix64(key + 0x52), key_c = mix64(key + 0x43);
+    uint64_t *col = (uint64_t *)malloc((size_t)c * 8);
+    for (uint64_t b = 0; b < c; ++b) {
+        uint64_t lo = b * cols / c, hi = (b + 1) * cols / c;
+        col[b] = lo + mix64(key_c + (b + 1) * 0x9E3779B97F4A7C15ull) % (hi - lo);
+    }
+    for (uint64_t a = 0; a < r; ++a) {
+        uint64_t lo = a * rows / r, hi = (a + 1) * rows / r;
+        uint64_t row = lo + mix64(key_r + (a + 1) * 0x9E3779B97F4A7C15ull) % (hi - lo);
+        for (uint64_t b = 0; b < c; ++b) out[a * c + b] = row * cols + col[b];
+    }
+    free(col);
+}
+
 /* ------------------------------------------------------------------ */
 /* Finalize: raw metrics, normalisation (App. A) and risk (Eq. 9)      */
 /* ------------------------------------------------------------------ */
