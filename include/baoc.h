@@ -214,11 +214,16 @@ int baoc_profile_end(baoc_profiler* p);
  * (one coordinate out of each of |Omega_i| equal strata, by a 64-bit mix of
  * (seed, block, stratum)), indices ascending.  The sampler packs g[Omega] of all
  * blocks into a compact buffer; the profiler then runs on that buffer with the
- * compact block layout.  Compact blocks carry no matrix shape. */
+ * compact block layout.
+ * Matrix blocks (rows, cols >= 2) keep a matrix form, which the structure residual of Eq. 7 needs:
+ * their Omega is a product of r = round(rows sqrt(ratio)) rows and c columns, c the least count with
+ * r c >= ceil(ratio d_i), each axis drawn by the same stratified rule, and the compact block is that
+ * r x c sub-matrix, row-major (so |Omega_i| may exceed ceil(ratio d_i) by less than r).  When r or c would
+ * be below 2 the block is sampled as a plain vector and its compact block carries no shape (F = 0). */
 typedef struct baoc_sampler baoc_sampler;
 
 /* Compact layout for this ratio (0 < ratio <= 1): out_compact (HOST, n_blocks, may
- * be NULL) receives offset/numel of each block in the compact buffer (starts on
+ * be NULL) receives offset/numel and the sub-matrix shape of each block in the compact buffer (starts on
  * multiples of 64 elements), out_compact_numel its length, out_workspace_bytes the
  * device bytes the sampler needs (tables + 8 bytes per sampled coordinate). */
 int baoc_sample_layout(const baoc_block* blocks, uint32_t n_blocks, double ratio,

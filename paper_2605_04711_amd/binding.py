@@ -283,7 +283,7 @@ class Sampler:
         cn, wb = C.c_uint64(), C.c_uint64()
         _check(self.lib.baoc_sample_layout(self._blocks, self.n_blocks, float(ratio), compact, C.byref(cn), C.byref(wb)),
                "baoc_sample_layout")
-        self.compact_blocks = [(b.offset, b.numel, 0, 0) for b in compact]
+        self.compact_blocks = [(b.offset, b.numel, b.rows, b.cols) for b in compact]
         self.compact_numel = cn.value
         self.device = torch.device(device)
         self.workspace = torch.empty(max(wb.value, 256), dtype=torch.uint8, device=self.device)

@@ -5,6 +5,10 @@
 //
 // Draw: stratified uniform -- stratum j of block i is [floor(j d/k), floor((j+1) d/k)),
 // one coordinate of each by a 64-bit mix of (seed, block, j); indices ascend.
+// A matrix block (rows x cols, both >= 2) keeps a matrix form, which Eq. 7 needs: Omega is a product of
+// r rows and c columns, r = round(rows sqrt(s)), c the least count with r c >= ceil(s d), each axis drawn
+// by the same stratified rule; the compact block is the r x c sub-matrix, row-major.  A sample too thin for
+// that (r < 2 or c < 2) falls back to the flat draw and carries no shape.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -21,7 +25,10 @@ struct alignas(8) SampleRow {
     uint64_t numel;           // d_i
     uint64_t count;           // k_i = |Omega_i|
     uint64_t idx_start;       // first entry of the block in the index table
-    uint32_t first_tile, pad_;
+    uint32_t first_tile;
+    uint32_t rows, cols;      // matrix shape of the block, or 0, 0
+    uint32_t sub_rows, sub_cols;   // shape of the sampled sub-matrix (product form), or 0, 0 for the flat draw
+    uint32_t pad_;
 };
 
 constexpr uint32_t kTile = 1024;    // samples per workgroup
@@ -51,6 +58,18 @@ __global__ __launch_bounds__(256) void k_draw(const SampleRow* __restrict__ rows
     const SampleRow r = rows[b];
     const uint64_t key = mix64(mix64(seed) + b);
     const uint64_t j0 = (uint64_t)(blockIdx.x - r.first_tile) * kTile;
+    if (r.sub_rows) {                                      // product form: sample j is (row a, column c) of the sub-matrix
+        const uint64_t key_r = mix64(key + 0x52), key_c = mix64(key + 0x43);
+        for (uint64_t j = j0 + threadIdx.x; j < min(r.count, j0 + kTile); j += 256) {
+            const uint64_t a = j / r.sub_cols, c = j - a * r.sub_cols;
+            const uint64_t rlo = a * r.rows / r.sub_rows, rhi = (a + 1) * r.rows / r.sub_rows;
+            const uint64_t clo = c * r.cols / r.sub_cols, chi = (c + 1) * r.cols / r.sub_cols;
+            const uint64_t row = rlo + mix64(key_r + (a + 1) * 0x9E3779B97F4A7C15ull) % (rhi - rlo);
+            const uint64_t col = clo + mix64(key_c + (c + 1) * 0x9E3779B97F4A7C15ull) % (chi - clo);
+            idx[r.idx_start + j] = r.src_offset + row * r.cols + col;
+        }
+        return;
+    }
     for (uint64_t j = j0 + threadIdx.x; j < min(r.count, j0 + kTile); j += 256) {
         const uint64_t lo = (uint64_t)(((unsigned __int128)j * r.numel) / r.count);
         const uint64_t hi = (uint64_t)(((unsigned __int128)(j + 1) * r.numel) / r.count);
@@ -81,12 +100,21 @@ int make_rows(const baoc_block* blocks, uint32_t n, double ratio, std::vector<Sa
     for (uint32_t i = 0; i < n; ++i) {
         const baoc_block& b = blocks[i];
         if (b.numel == 0 || b.offset + b.numel < b.offset) return BAOC_ERR_INVALID;
+        if ((b.rows || b.cols) && (uint64_t)b.rows * b.cols != b.numel) return BAOC_ERR_INVALID;
         double k = std::ceil(ratio * (double)b.numel);                // |Omega_i| = ceil(s d_i), in [1, d_i]
         if (!(k >= 1.0)) k = 1.0;
         if (k > (double)b.numel) k = (double)b.numel;
         SampleRow& r = (*rows)[i];
         dst = (dst + 63) / 64 * 64;                                    // compact blocks start on 64 elements
         r.src_offset = b.offset; r.dst_offset = dst; r.numel = b.numel; r.count = (uint64_t)k;
+        r.rows = b.rows; r.cols = b.cols; r.sub_rows = r.sub_cols = 0;
+        if (b.rows >= 2 && b.cols >= 2) {                              // matrix form of the sample (Eq. 7)
+            double rr = std::floor((double)b.rows * std::sqrt(ratio) + 0.5);
+            if (!(rr >= 1.0)) rr = 1.0;
+            if (rr > (double)b.rows) rr = (double)b.rows;
+            const uint64_t sr = (uint64_t)rr, sc = std::min<uint64_t>(b.cols, (r.count + sr - 1) / sr);
+            if (sr >= 2 && sc >= 2) { r.sub_rows = (uint32_t)sr; r.sub_cols = (uint32_t)sc; r.count = sr * sc; }
+        }
         r.idx_start = idx; r.first_tile = (uint32_t)tiles; r.pad_ = 0;
         dst += r.count; idx += r.count; tiles += (r.count + kTile - 1) / kTile;
         if (tiles > 0x7fffffffull) return BAOC_ERR_UNSUPPORTED;
@@ -115,7 +143,7 @@ extern "C" int baoc_sample_layout(const baoc_block* blocks, uint32_t n_blocks, d
     const int rc = make_rows(blocks, n_blocks, ratio, &rows, &cn, &tot, &tiles, &end);
     if (rc) return rc;
     if (out_compact)
-        for (uint32_t i = 0; i < n_blocks; ++i) out_compact[i] = baoc_block{rows[i].dst_offset, rows[i].count, 0, 0};
+        for (uint32_t i = 0; i < n_blocks; ++i) out_compact[i] = baoc_block{rows[i].dst_offset, rows[i].count, rows[i].sub_rows, rows[i].sub_cols};
     if (out_compact_numel) *out_compact_numel = cn;
     if (out_workspace_bytes) *out_workspace_bytes = rows_bytes(n_blocks) + tot * 8;
     return BAOC_OK;

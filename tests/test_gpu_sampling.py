@@ -18,13 +18,17 @@ def test_index_sets_gather_and_sampled_statistics(env, dtype, ratio):  # noqa: F
     w = ragged_workload(dtype, 1)
     seed = 17
     smp = binding.Sampler(w.blocks, ratio, seed)
-    idx = []
+    idx, shapes = [], []
     for i, b in enumerate(w.blocks):
-        want = oracle.sample_indices(b.numel, ratio, seed, i) + np.uint64(b.offset)
+        want, shape = oracle.sample_indices_block(b.numel, b.rows, b.cols, ratio, seed, i)     # sub-matrix for matrix blocks
+        want = want + np.uint64(b.offset)
         got = smp.indices(i).cpu().numpy().view(np.uint64)
         assert np.array_equal(got, want), f"Omega of block {i}"
-        assert smp.compact_blocks[i][1] == oracle.sample_count(b.numel, ratio)
-        idx.append(want.astype(np.int64))
+        assert smp.compact_blocks[i][1] == want.size and tuple(smp.compact_blocks[i][2:]) == shape
+        if shape == (0, 0):
+            assert want.size == oracle.sample_count(b.numel, ratio)
+        idx.append(want.astype(np.int64)); shapes.append(shape)
+    assert any(sh != (0, 0) for sh in shapes) or ratio < 0.01
     params = binding.default_profile_params(grad_dtype=1 if dtype == "bf16" else 0)
     prof = binding.Profiler(smp.compact_blocks, params)
     orc = [oracle.Block(len(ix), **oracle_params(params)) for ix in idx]
@@ -41,7 +45,8 @@ def test_index_sets_gather_and_sampled_statistics(env, dtype, ratio):  # noqa: F
         prof.step(compact)
     stats, _ = prof.finalize()
     for i in range(len(idx)):
-        assert_stats_close(stats[i], orc[i].finalize(), f"sampled block {i} ratio {ratio}")
+        F = orc[i].structure_residual(*shapes[i])                    # Eq. 7 on the sampled sub-matrix
+        assert_stats_close(stats[i], orc[i].finalize(F_raw=F), f"sampled block {i} ratio {ratio}")
 
 
 def test_sampler_writes_stay_inside_its_buffers(env):  # noqa: F811
@@ -93,8 +98,9 @@ def test_full_size_sampling_of_the_7b_layout(env):  # noqa: F811
     torch.cuda.synchronize()
     for i in (0, 1, 2, 150, 289, 290):
         b = w.blocks[i]
-        want = oracle.sample_indices(b.numel, 0.001, 5, i).astype(np.int64) + b.offset
-        assert np.array_equal(smp.indices(i).cpu().numpy(), want)
+        want, shape = oracle.sample_indices_block(b.numel, b.rows, b.cols, 0.001, 5, i)
+        want = want.astype(np.int64) + b.offset
+        assert np.array_equal(smp.indices(i).cpu().numpy(), want) and tuple(smp.compact_blocks[i][2:]) == shape
         o, n = smp.compact_blocks[i][0], smp.compact_blocks[i][1]
         assert torch.equal(compact[o:o + n], buf[torch.from_numpy(want).cuda()])
 
