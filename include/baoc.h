@@ -169,8 +169,11 @@ int baoc_profile_begin_static(const baoc_block* blocks, uint32_t n_blocks,
  * begin) and the per-block reduction.  Returns without waiting.  The gradient
  * buffer must stay valid until that stream work has run; afterwards the
  * caller may overwrite it (the library keeps its own copy of g_t as g_{t-1}).
- * Consecutive calls are consecutive samples.  The step index is a launch argument kept
- * on the host, so a captured HIP graph of this call must not be replayed as a later step.
+ * Consecutive calls are consecutive samples.  The first call after begin launches another
+ * kernel than the later ones (the states are known to be zero); from the second call on
+ * the launches are the same for every step (the step count is kept on the device), so a HIP
+ * graph captured from a later call may be replayed once per further step, with the next
+ * gradient in the same buffer.
  * Range: the sums of squares of a
  * chunk are kept in fp32 before the fp64 stage, so gradient magnitudes up to about
  * 1e8 give finite statistics (beyond, sums of v^2 overflow and the error and noise

@@ -414,7 +414,7 @@ __global__ __launch_bounds__(256) void k_slab_reduce(const float* __restrict__ p
 //   the first cosine initialises rho_bar, later ones enter with weight 1 - beta_rho.
 __global__ __launch_bounds__(256) void k_block_reduce(
     const float* __restrict__ partials, const double* __restrict__ slab_sums, const BlockRow* __restrict__ rows,
-    double* __restrict__ rec_all, uint32_t step, double beta_rho, double eps)
+    double* __restrict__ rec_all, double beta_rho, double eps)
 {
     const BlockRow br = rows[blockIdx.x];
     double* rec = rec_all + (uint64_t)blockIdx.x * kRecDoubles;
@@ -452,6 +452,9 @@ __global__ __launch_bounds__(256) void k_block_reduce(
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        // The step index lives in the block's record, not in a launch argument: a captured launch of a
+        // steady-state step can be replayed for later steps.
+        const uint32_t step = (uint32_t)rec[R_STEPS] + 1u;
         const double S_gg = rec[S_GG], S_gp = rec[S_GP];
         if (step >= 2) {
             double c = S_gp / (sqrt(S_gg) * sqrt(rec[R_SPP]) + eps);
@@ -1529,7 +1532,7 @@ extern "C" int baoc_profile_step(baoc_profiler* h, const void* d_grad_flat, uint
                            part, reinterpret_cast<const Slab*>(h->ws + P.off_slabs), slab_sums);
     hipLaunchKernelGGL(k_block_reduce, dim3((uint32_t)P.rows.size()), dim3(256), 0, st,
                        part, slab_sums, reinterpret_cast<const BlockRow*>(h->ws + P.off_rows),
-                       reinterpret_cast<double*>(h->ws + P.off_rec), h->steps, q.beta_rho, q.eps);
+                       reinterpret_cast<double*>(h->ws + P.off_rec), q.beta_rho, q.eps);
     if (hipGetLastError() != hipSuccess) { h->sticky = BAOC_ERR_HIP; return BAOC_ERR_HIP; }
     return BAOC_OK;
 }

@@ -423,6 +423,40 @@ def test_ragged_blocks_other_seeds(env, dtype, seed):
     run_both(env, w, 5, seed=seed, theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
 
 
+def test_captured_step_replays_as_later_steps(env):
+    """A HIP graph captured from a steady-state step is replayed for the following steps (the step count lives on
+    the device): same bits as eager steps on the same gradients, checked after every replay, with eager work and
+    synchronisations between the replays."""
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = ragged_workload("bf16", 64)
+    params = binding.default_profile_params(grad_dtype=1)
+    grads = [device.fill(w, device.new_buffer(w), 41, t).clone() for t in range(1, 8)]
+    prof, ref = binding.Profiler(w.blocks, params), binding.Profiler(w.blocks, params)
+    gbuf = torch.zeros_like(grads[0])                      # the buffer the captured launch reads
+    for t in (0, 1):
+        gbuf.copy_(grads[t]); prof.step(gbuf); ref.step(grads[t])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        prof.step(gbuf)                                    # captured, not run
+    for t in range(2, 7):
+        gbuf.copy_(grads[t])
+        graph.replay()
+        ref.step(grads[t])                                 # eager work between the replays
+        torch.cuda.synchronize()
+        a, b = prof.finalize(w.configs)[0], ref.finalize(w.configs)[0]
+        assert bytes(a) == bytes(b), f"after replay for step {t + 1}"
+        assert a[0].steps == t + 1 and a[0].n_cos == t
+    orc = OracleRunner(w.blocks, None, **oracle_params(params))
+    for g in grads:
+        orc.step_from_device(g)
+    stats, risk = prof.finalize(w.configs)
+    ostats, orisk = orc.finalize(w.configs, shapes=[(b.rows, b.cols) for b in w.blocks])
+    for i in range(len(w.blocks)):
+        assert_stats_close(stats[i], ostats[i], f"graph block {i}")
+    assert_risk_close(risk, orisk, "graph")
+
+
 def test_error_paths(env):
     torch, binding = env["torch"], env["binding"]
     prof = binding.Profiler([(0, 100), (200, 50)])
