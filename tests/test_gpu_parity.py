@@ -423,6 +423,37 @@ def test_ragged_blocks_other_seeds(env, dtype, seed):
     run_both(env, w, 5, seed=seed, theta_dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mostly_dead_coordinates_overflow_the_candidate_lists(env, dtype):
+    """60 % of the coordinates never see a gradient (v = 0 exactly), so the 0.1 quantile sits in a bin that
+    holds most of every tile: the candidate lists of the matrix blocks overflow and their last digit comes from
+    the third scan of v, while the block next to them (no dead coordinates) stays on its lists."""
+    torch, binding = env["torch"], env["binding"]
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    blocks = [W._mat("dead", 600, 520), W._vec("vec", 5000), W._mat("alive", 300, 260), W._mat("thin", 1030, 3)]
+    w = W.Workload("dead", blocks, 3, dtype, "cycle", **W.K6)
+    W.layout(w, 64)
+    params = binding.default_profile_params(grad_dtype=0 if dtype == "f32" else 1)
+    prof = binding.Profiler(w.blocks, params)
+    orc = OracleRunner(w.blocks, None, **oracle_params(params))
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(99)
+    dead = torch.rand(w.buffer_numel, device="cuda:0", generator=gen) < 0.6
+    lo, hi = w.blocks[2].offset, w.blocks[2].offset + w.blocks[2].numel
+    dead[lo:hi] = False
+    for _ in range(3):
+        g = torch.randn(w.buffer_numel, device="cuda:0", generator=gen) * 1e-3
+        g[dead] = 0.0
+        g = g.to(tdt)
+        prof.step(g); orc.step_from_device(g)
+    theta = (0.02 * torch.randn(w.buffer_numel, device="cuda:0", generator=gen)).to(tdt)
+    stats, risk = prof.finalize(w.configs, theta=theta)
+    ostats, orisk = orc.finalize(w.configs, shapes=[(b.rows, b.cols) for b in w.blocks], theta=theta)
+    assert stats[0].q10 == 0.0 and stats[2].q10 > 0.0
+    for i in range(len(w.blocks)):
+        assert_stats_close(stats[i], ostats[i], f"dead block {i}")
+    assert_risk_close(risk, orisk, "dead")
+
+
 def test_captured_step_replays_as_later_steps(env):
     """A HIP graph captured from a steady-state step is replayed for the following steps (the step count lives on
     the device): same bits as eager steps on the same gradients, checked after every replay, with eager work and
