@@ -77,6 +77,32 @@ def test_layout_validation():
     assert ws([(20, 10), (0, 20), (100, 7, 7, 1)]) > 0                     # any order, gaps, touching
 
 
+def test_sample_layout_matches_the_oracle_shapes_and_counts():
+    """baoc_sample_layout is host code: compact offsets, counts and sub-matrix shapes for every block of the
+    workloads, against the oracle's rule (flat draw: ceil(s d); matrix blocks: r x c with r = round(rows sqrt(s)))."""
+    lib = B.load_library()
+    for name in ("resnet50", "unet", "llama7b"):
+        w = W.make(name)
+        arr = binding._block_array(w.blocks)
+        for ratio in (0.001, 0.01, 0.1, 1.0):
+            compact = (binding.Block * len(w.blocks))()
+            cn, wb = C.c_uint64(), C.c_uint64()
+            assert lib.baoc_sample_layout(arr, len(w.blocks), ratio, compact, C.byref(cn), C.byref(wb)) == 0
+            end, total = 0, 0
+            for i, b in enumerate(w.blocks):
+                shape = oracle.sample_matrix_shape(b.rows, b.cols, ratio) if b.rows and b.cols else None
+                want = shape[0] * shape[1] if shape else oracle.sample_count(b.numel, ratio)
+                assert compact[i].numel == want and (compact[i].rows, compact[i].cols) == (shape or (0, 0)), (name, ratio, i)
+                assert compact[i].offset % 64 == 0 and compact[i].offset >= end
+                end = compact[i].offset + compact[i].numel; total += want
+            assert cn.value >= end and cn.value % 64 == 0 and wb.value >= 8 * total
+            if ratio == 1.0:
+                assert total == w.numel
+    bad = binding._block_array([(0, 12, 3, 5)])
+    assert lib.baoc_sample_layout(bad, 1, 0.5, None, None, None) == binding.ERR_INVALID      # rows * cols != numel
+    assert lib.baoc_sample_layout(arr, len(w.blocks), 0.0, None, None, None) == binding.ERR_INVALID
+
+
 def test_null_arguments_are_rejected():
     lib = B.load_library()
     assert lib.baoc_profile_step(None, None, 0, None) == binding.ERR_INVALID
