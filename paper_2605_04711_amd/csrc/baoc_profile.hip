@@ -795,6 +795,7 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
     uint32_t* __restrict__ hist_all, float eps, bool want_p)
 {
     __shared__ uint32_t h[kBins1];
+    __shared__ float rowsum[4][kTileRows];                // a tile's row sums, written out together at the end
     const uint32_t lane = threadIdx.x & 63u, wave = scalar_wave_index();
     for (uint32_t i = threadIdx.x; i < kBins1; i += 256) h[i] = 0;
     const MatTask t = decode_quad(mats, n_mats, blockIdx.x, wave);
@@ -808,7 +809,7 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
         // Column sums and the sum of p run over up to 256 rows per lane: kept in fp64 so that a constant
         // v (rank one, p constant) comes out as such to ~1e-7 instead of the ~1e-5 of a long fp32 chain.
         double cs[4] = {0.0, 0.0, 0.0, 0.0}, psum = 0.0;
-        float* rp = rowpart + m.off_rowpart + (uint64_t)t.row0 * m.n_tiles + t.tile;
+        float* rs_out = rowsum[wave];
         auto consume = [&](auto full, const float x[4]) {
             constexpr bool FULL = decltype(full)::value;     // every column of the lane is inside the tile
             float prow = 0.f;
@@ -845,7 +846,7 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
                     if (r + q >= t.row1) break;
                     const float x[4] = {cx[q].x, cx[q].y, cx[q].z, cx[q].w};
                     const float rs = consume(std::true_type(), x);
-                    if (lane == 0) rp[(uint64_t)(r + q - t.row0) * m.n_tiles] = rs;
+                    if (lane == 0) rs_out[r + q - t.row0] = rs;
                 }
             }
         } else {
@@ -853,9 +854,17 @@ __global__ __launch_bounds__(256) void k_tile_pass1(
                 float x[4];
                 load_tile_row(row, t.vec, lane, t.ncols, x);
                 const float rs = consume(std::false_type(), x);
-                if (lane == 0) *rp = rs;
-                row += m.cols; rp += m.n_tiles;
+                if (lane == 0) rs_out[r - t.row0] = rs;
+                row += m.cols;
             }
+        }
+        // row sums of this tile: rowpart is tile-major ([tile][row]), so the wavefront writes one run
+        {
+            float* rp = rowpart + m.off_rowpart + (uint64_t)t.tile * m.rows + t.row0;
+            const uint32_t nr = t.row1 - t.row0;
+#pragma unroll
+            for (uint32_t j = 0; j < kTileRows / 64; ++j)
+                if (lane + 64 * j < nr) rp[lane + 64 * j] = rs_out[lane + 64 * j];
         }
         float* cp = colpart + m.off_colpart + (uint64_t)t.seg * m.cols + t.col0;
 #pragma unroll
@@ -884,9 +893,9 @@ __global__ __launch_bounds__(256) void k_tile_finish1(const MatRow* __restrict__
     double local = 0.0, lp = 0.0;
     const uint32_t rper = (m.rows + kFinSlices - 1) / kFinSlices, i1 = min(m.rows, (y + 1) * rper);
     for (uint32_t i = y * rper + threadIdx.x; i < i1; i += 256) {
-        const float* rp = rowpart + m.off_rowpart + (uint64_t)i * m.n_tiles;
+        const float* rp = rowpart + m.off_rowpart + i;                       // tile-major: [tile][row]
         double s = 0.0;
-        for (uint32_t t = 0; t < m.n_tiles; ++t) s += (double)rp[t];
+        for (uint32_t t = 0; t < m.n_tiles; ++t) s += (double)rp[(uint64_t)t * m.rows];
         const double r = s / (double)m.cols;
         rvec[m.off_r + i] = (float)r;
         local += r;
