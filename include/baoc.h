@@ -289,8 +289,8 @@ int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units
                    const double* weights, double alpha,
                    uint32_t* out_block_of_unit, uint32_t* out_n_blocks, double* out_tau);
 
-/* Cap on the states baoc_allocate keeps over all levels of its recursion (24 bytes each), for this
- * thread's later calls; 0 = default (32 M).  Beyond it the call returns BAOC_ERR_LIMIT. */
+/* Cap on the states baoc_allocate keeps over all levels of any one of its recursions (24 bytes each), for
+ * this thread's later calls; 0 = default (32 M).  Beyond it the call returns BAOC_ERR_LIMIT. */
 void baoc_allocate_set_node_limit(uint64_t max_nodes);
 
 const char* baoc_status_string(int status);

@@ -3,23 +3,30 @@
 // exclusions of Sec. 3.2 and a canonical answer (lexicographically smallest
 // optimum of the integer image of the instance).
 //
-// Method: a list recursion from the last block backwards, then the answer block by block.
-//   Lists.  lists[i] holds suffix states (Z, W, T) = sums of (phi, mem, tau) over some choice for
-//   the blocks i..N-1.  A state is dropped when
-//     - no prefix can complete it within the budgets (least use of each row by the blocks before i),
-//     - a Lagrangian bound of the blocks before i shows that no completion reaches the cutoff (weak
+// Method: list recursions over the blocks, three in a row.
+//   Lists.  For one ordering of the blocks ("levels"), lists[i] holds states (Z, W, T) = sums of
+//   (phi, mem, tau) over some choice for the levels i..N-1.  A state is dropped when
+//     - no choice for the levels before i can complete it within the budgets (least use of each row),
+//     - a Lagrangian bound of the levels before i shows that no completion reaches the cutoff (weak
 //       duality, decided in floating point and, on a near miss, exactly in 128-bit integers, for a small
 //       grid of multiplier pairs around the maximiser of the dual of the whole instance), or
 //     - another state of the same level is no larger in all of Z, W and T: whatever completes the worse
 //       one completes the better one too, with a total no larger.
-//   A row that no prefix can push over its budget any more does not constrain a state: its use is
+//   A row that no earlier level can push over its budget any more does not constrain a state: its use is
 //   raised to that threshold, so that more states undercut each other.
-//   Cutoffs rise from the smallest lattice value the bound of the whole instance allows (all totals lie
-//   on base + g Z, g the gcd of the phi differences inside the blocks): a run that ends empty proves that
-//   the optimum lies above its cutoff; the first run that reaches level 0 holds the optimum Z*.
-//   Answer.  The lists of that run hold, for every optimal assignment and every i, a state that undercuts
-//   its suffix.  So the lexicographically smallest optimum is read off in index order: block i takes the
-//   smallest configuration for which some state of lists[i+1] completes the prefix to Z* within both rows.
+//   1. The optimal value Z*.  Levels ordered by how firmly the multipliers decide a block (undecided blocks
+//      first, i.e. processed last).  Cutoffs rise from the smallest lattice value the bound of the whole
+//      instance allows (all totals lie on base + g Z, g the gcd of the phi differences inside the blocks): a
+//      run that ends empty proves that the optimum lies above its cutoff; the first run that reaches level 0
+//      holds Z*.
+//   2. The configurations that occur in optimal assignments at all: a forward pass over the same levels keeps
+//      a state of the levels before i, extended by a configuration of level i, when a state of lists[i+1]
+//      completes it to Z* within both rows.
+//   3. The canonical optimum.  The recursion once more in index order, over those configurations only, with
+//      Z* as cutoff.  Its lists hold, for every optimal assignment and every i, a state that undercuts the
+//      assignment's part on the blocks i..N-1, so the lexicographically smallest optimum is read off in
+//      index order: block i takes the smallest configuration for which some state of lists[i+1] completes
+//      the prefix to Z* within both rows.
 // The lists are capped by a node limit: when it is hit the call fails rather than return a guess.
 #include <algorithm>
 #include <cmath>
@@ -163,7 +170,7 @@ Multiplier to_integer(double l1, double l2)
     return m;
 }
 
-// A suffix state: sums of (phi, mem, tau) over the blocks i..N-1 of some choice for them.
+// A partial state: sums of (phi, mem, tau) over some choice for a run of consecutive levels.
 struct State { int64_t Z, W, T; };
 
 int64_t gcd64(int64_t a, int64_t b)
@@ -174,23 +181,194 @@ int64_t gcd64(int64_t a, int64_t b)
     return a;
 }
 
+// For states added in any order: the least Z among those added with time <= t.
+struct Stair {
+    std::vector<std::pair<int64_t, int64_t>> e;        // (T, least Z among the added states with time <= T), T ascending, Z descending
+    void clear() { e.clear(); }
+    int64_t least(int64_t t) const
+    {
+        auto it = std::upper_bound(e.begin(), e.end(), t, [](int64_t x, const std::pair<int64_t, int64_t>& y) { return x < y.first; });
+        return it == e.begin() ? kInf64 : std::prev(it)->second;
+    }
+    void add(int64_t t, int64_t z)
+    {
+        auto it = std::upper_bound(e.begin(), e.end(), t, [](int64_t x, const std::pair<int64_t, int64_t>& y) { return x < y.first; });
+        if (it != e.begin() && std::prev(it)->second <= z) return;
+        if (it != e.begin() && std::prev(it)->first == t) { --it; it->second = z; }
+        else it = e.insert(it, std::make_pair(t, z));
+        auto nx = std::next(it), r = nx;
+        while (r != e.end() && r->second >= z) ++r;      // entries to the right that are no better
+        e.erase(nx, r);
+    }
+};
+
+// Keep the states that no other one undercuts (no larger in all of Z, W, T; of equal states one stays), in the
+// order (W, T, Z) ascending.
+void keep_undercut_free(std::vector<State>& cand, std::vector<State>& out, std::vector<uint32_t>& order, Stair& stair)
+{
+    const size_t n = cand.size();
+    out.clear();
+    order.resize(n);
+    for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
+    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        const State &x = cand[a], &y = cand[b];
+        if (x.W != y.W) return x.W < y.W;
+        if (x.T != y.T) return x.T < y.T;
+        return x.Z < y.Z;
+    });
+    stair.clear();
+    for (uint32_t j : order) {
+        const State& s = cand[j];
+        if (stair.least(s.T) <= s.Z) continue;             // undercut (or equalled) by a state swept before
+        stair.add(s.T, s.Z);
+        out.push_back(s);
+    }
+}
+
+enum { kRunOk = 0, kRunEmpty = 1, kRunLimit = 3 };
+
+// The list recursion over one ordering of the blocks ("levels"): lists[i] holds states of the levels i..N-1.
+struct Levels {
+    const Instance& I;
+    const std::vector<Multiplier>& mult;
+    uint32_t N;
+    size_t M;
+    // least and largest use of each row by the levels before i, for feasibility and for the clamp
+    std::vector<int64_t> preMinW, preMinT, preMaxW, preMaxT;
+    // preRC[m][i] = sum over the levels before i of the least reduced cost, minus the budget terms; and the
+    // double images of the multipliers: a bound far from the cutoff is decided in floating point, only a near
+    // miss is evaluated exactly
+    std::vector<std::vector<i128>> preRC;
+    std::vector<double> Sd, L1d, L2d;
+    std::vector<std::vector<double>> preRCd;
+    std::vector<std::vector<State>> lists;
+    std::vector<State> cand;
+    std::vector<uint32_t> order;
+    Stair stair;
+
+    Levels(const Instance& inst, const std::vector<Multiplier>& m)
+        : I(inst), mult(m), N(inst.N), M(m.size()), preMinW(N + 1, 0), preMinT(N + 1, 0), preMaxW(N + 1, 0), preMaxT(N + 1, 0),
+          preRC(M, std::vector<i128>(N + 1)), Sd(M), L1d(M), L2d(M), preRCd(M, std::vector<double>(N + 1)), lists(N + 1)
+    {
+        for (uint32_t i = 0; i < N; ++i) {
+            int64_t lw = kInf64, lt = kInf64, hw = -kInf64, ht = -kInf64;
+            for (const Item& it : I.items[i]) {
+                lw = std::min(lw, it.w); lt = std::min(lt, it.t); hw = std::max(hw, it.w); ht = std::max(ht, it.t);
+            }
+            preMinW[i + 1] = preMinW[i] + lw; preMinT[i + 1] = preMinT[i] + lt;
+            preMaxW[i + 1] = preMaxW[i] + hw; preMaxT[i + 1] = preMaxT[i] + ht;
+        }
+        for (size_t k = 0; k < M; ++k) {
+            preRC[k][0] = -(mult[k].L1 * (i128)I.B1 + mult[k].L2 * (i128)I.B2);
+            for (uint32_t i = 0; i < N; ++i) {
+                i128 best = 0; bool first = true;
+                for (const Item& it : I.items[i]) {
+                    const i128 rc = (i128)it.phi * mult[k].S + mult[k].L1 * (i128)it.w + mult[k].L2 * (i128)it.t;
+                    if (first || rc < best) { best = rc; first = false; }
+                }
+                preRC[k][i + 1] = preRC[k][i] + best;
+            }
+            Sd[k] = (double)mult[k].S; L1d[k] = (double)mult[k].L1; L2d[k] = (double)mult[k].L2;
+            for (uint32_t i = 0; i <= N; ++i) preRCd[k][i] = (double)preRC[k][i];
+        }
+    }
+
+    // Build the lists from the last level backwards.  A run that ends with states at level 0 has kept, for every
+    // feasible assignment of value <= cutoff and every i, a state of lists[i] that undercuts (or equals) the part
+    // of the assignment on the levels i..N-1.
+    int run(int64_t cutoff, uint64_t limit)
+    {
+        uint64_t total = 1;
+        lists[N].assign(1, State{0, 0, 0});
+        for (int i = (int)N - 1; i >= 0; --i) {
+            // A row that no choice for the levels before i can push over its budget any more is not a constraint
+            // for the state: below the threshold every value is as good as the threshold itself, which lets more
+            // states undercut others.
+            const int64_t floorW = I.B1 - preMaxW[i], floorT = I.B2 - preMaxT[i];
+            cand.clear();
+            for (const State& s : lists[i + 1]) {
+                for (const Item& it : I.items[i]) {
+                    State c{s.Z + it.phi, std::max(s.W + it.w, floorW), std::max(s.T + it.t, floorT)};
+                    if (c.W + preMinW[i] > I.B1 || c.T + preMinT[i] > I.B2) continue;
+                    bool cut = false;
+                    for (size_t m = 0; m < M && !cut; ++m) {
+                        const double a = (double)c.Z * Sd[m], b = L1d[m] * (double)c.W, d = L2d[m] * (double)c.T;
+                        const double lhs_d = a + b + d + preRCd[m][i], rhs_d = (double)cutoff * Sd[m];
+                        const double tol = 1e-9 * (std::fabs(a) + std::fabs(b) + std::fabs(d) + std::fabs(preRCd[m][i]) + std::fabs(rhs_d));
+                        if (lhs_d > rhs_d + tol) { cut = true; break; }
+                        if (lhs_d < rhs_d - tol) continue;
+                        const i128 lhs = (i128)c.Z * mult[m].S + mult[m].L1 * (i128)c.W + mult[m].L2 * (i128)c.T + preRC[m][i];
+                        cut = lhs > (i128)cutoff * mult[m].S;
+                    }
+                    if (cut) continue;
+                    cand.push_back(c);
+                }
+            }
+            if (cand.empty()) return kRunEmpty;
+            keep_undercut_free(cand, lists[i], order, stair);
+            total += lists[i].size();
+            if (total > limit) return kRunLimit;
+        }
+        return kRunOk;
+    }
+
+    // After a run that reached level 0 with a cutoff >= z: which configurations occur in some feasible assignment
+    // of value <= z.  Forward over the levels: front holds states of the levels before i (true sums); a state
+    // extended by a configuration is kept when some state of lists[i+1] completes it within z and both budgets,
+    // and the configuration is marked.  Exact in both directions: a kept pair is an assignment, and the part of
+    // any assignment of value <= z before and after level i is undercut by a state of front and of lists[i+1].
+    int viable(int64_t z, uint64_t limit, std::vector<std::vector<uint8_t>>& mark)
+    {
+        struct Ext { State s; uint32_t k; };
+        std::vector<Ext> ext;
+        std::vector<State> front(1, State{0, 0, 0}), kept;
+        uint64_t total = 1;
+        mark.assign(N, std::vector<uint8_t>());
+        for (uint32_t i = 0; i < N; ++i) {
+            mark[i].assign(I.items[i].size(), 0);
+            ext.clear();
+            for (const State& p : front)
+                for (uint32_t k = 0; k < I.items[i].size(); ++k) {
+                    const Item& it = I.items[i][k];
+                    ext.push_back(Ext{State{p.Z + it.phi, p.W + it.w, p.T + it.t}, k});
+                }
+            // most room in the memory row last: the states of lists[i+1] come in ascending W and enter the staircase as they fit
+            std::sort(ext.begin(), ext.end(), [](const Ext& a, const Ext& b) { return a.s.W > b.s.W; });
+            stair.clear();
+            const std::vector<State>& next = lists[i + 1];
+            size_t at = 0;
+            kept.clear();
+            for (const Ext& q : ext) {
+                const int64_t roomW = I.B1 - q.s.W, roomT = I.B2 - q.s.T;
+                while (at < next.size() && next[at].W <= roomW) { stair.add(next[at].T, next[at].Z); ++at; }
+                if (stair.least(roomT) <= z - q.s.Z) { mark[i][q.k] = 1; kept.push_back(q.s); }
+            }
+            if (kept.empty()) return kRunEmpty;
+            keep_undercut_free(kept, front, order, stair);
+            total += front.size();
+            if (total > limit) return kRunLimit;
+        }
+        return kRunOk;
+    }
+};
+
 int solve(const Instance& I, std::vector<uint32_t>& answer)
 {
     const uint32_t N = I.N;
-    // least and largest use of each row by the blocks before i (prefixes), for feasibility and for the clamp
-    std::vector<int64_t> preMinW(N + 1, 0), preMinT(N + 1, 0), preMaxW(N + 1, 0), preMaxT(N + 1, 0);
     int64_t g = 0;                                     // all totals lie on one lattice base + g Z
-    for (uint32_t i = 0; i < N; ++i) {
-        int64_t lw = kInf64, lt = kInf64, hw = -kInf64, ht = -kInf64;
-        for (const Item& it : I.items[i]) {
-            lw = std::min(lw, it.w); lt = std::min(lt, it.t); hw = std::max(hw, it.w); ht = std::max(ht, it.t);
-            g = gcd64(g, it.phi - I.items[i][0].phi);
+    {
+        int64_t minW = 0, minT = 0;
+        for (uint32_t i = 0; i < N; ++i) {
+            int64_t lw = kInf64, lt = kInf64;
+            for (const Item& it : I.items[i]) {
+                lw = std::min(lw, it.w); lt = std::min(lt, it.t);
+                g = gcd64(g, it.phi - I.items[i][0].phi);
+            }
+            minW += lw; minT += lt;
         }
-        preMinW[i + 1] = preMinW[i] + lw; preMinT[i + 1] = preMinT[i] + lt;
-        preMaxW[i + 1] = preMaxW[i] + hw; preMaxT[i + 1] = preMaxT[i] + ht;
+        if (minW > I.B1 || minT > I.B2) return BAOC_ERR_INFEASIBLE;
     }
     if (g == 0) g = 1;
-    if (preMinW[N] > I.B1 || preMinT[N] > I.B2) return BAOC_ERR_INFEASIBLE;
 
     // multipliers: alternate the two one-dimensional dual maximisations a few times, then polish the pair by a
     // pattern search on the dual value (alternation alone can stall at a kink of the piecewise linear dual)
@@ -234,28 +412,7 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
             mult.push_back(to_integer(l1 * std::pow(1.05, a), l2 * std::pow(1.05, b)));
         }
     if (l1 > 0 && l2 > 0) { mult.push_back(to_integer(l1, 0.0)); mult.push_back(to_integer(0.0, l2)); }
-    const size_t M = mult.size();
-    // preRC[m][i] = sum over the blocks before i of the least reduced cost, minus the budget terms
-    std::vector<std::vector<i128>> preRC(M, std::vector<i128>(N + 1));
-    for (size_t m = 0; m < M; ++m) {
-        preRC[m][0] = -(mult[m].L1 * (i128)I.B1 + mult[m].L2 * (i128)I.B2);
-        for (uint32_t i = 0; i < N; ++i) {
-            i128 best = 0; bool first = true;
-            for (const Item& it : I.items[i]) {
-                const i128 rc = (i128)it.phi * mult[m].S + mult[m].L1 * (i128)it.w + mult[m].L2 * (i128)it.t;
-                if (first || rc < best) { best = rc; first = false; }
-            }
-            preRC[m][i + 1] = preRC[m][i] + best;
-        }
-    }
-    // double images of the multipliers: a bound far from the cutoff is decided in floating point,
-    // only a near miss is evaluated exactly
-    std::vector<double> Sd(M), L1d(M), L2d(M);
-    std::vector<std::vector<double>> preRCd(M, std::vector<double>(N + 1));
-    for (size_t m = 0; m < M; ++m) {
-        Sd[m] = (double)mult[m].S; L1d[m] = (double)mult[m].L1; L2d[m] = (double)mult[m].L2;
-        for (uint32_t i = 0; i <= N; ++i) preRCd[m][i] = (double)preRC[m][i];
-    }
+
     int64_t z_max = 0;                                 // no assignment costs more than this
     for (uint32_t i = 0; i < N; ++i) {
         int64_t mx = I.items[i][0].phi;
@@ -263,82 +420,31 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
         z_max += mx;
     }
     const int64_t ub = H.have ? H.Z : z_max;           // some feasible assignment has a total <= ub (or none exists)
-
     const uint64_t limit = g_node_limit ? g_node_limit : kDefaultNodeLimit;
-    // lists[i]: suffix states of the blocks i..N-1 that some prefix may still complete to a feasible
-    // assignment of value <= cutoff, none of them undercut by another in all of (Z, W, T)
-    std::vector<std::vector<State>> lists(N + 1);
-    std::vector<State> cand;
-    std::vector<uint32_t> order;
-    std::vector<std::pair<int64_t, int64_t>> stair;    // (T, least Z among the states swept so far with time <= T), T ascending, Z descending
 
-    enum { kRunOk = 0, kRunEmpty = 1, kRunLimit = 3 };
-    // run(cutoff): build the lists from the last block backwards.  A run that ends with states at level 0
-    // has kept, for every feasible assignment of value <= cutoff and every i, a state of lists[i] that
-    // undercuts (or equals) its suffix i..N-1.
-    auto run = [&](int64_t cutoff) -> int {
-        uint64_t total = 1;
-        lists[N].assign(1, State{0, 0, 0});
-        for (int i = (int)N - 1; i >= 0; --i) {
-            // A row that no prefix can push over its budget any more is not a constraint for the state: below
-            // the threshold every value is as good as the threshold itself, which lets more states undercut others.
-            const int64_t floorW = I.B1 - preMaxW[i], floorT = I.B2 - preMaxT[i];
-            cand.clear();
-            for (const State& s : lists[i + 1]) {
-                for (const Item& it : I.items[i]) {
-                    State c{s.Z + it.phi, std::max(s.W + it.w, floorW), std::max(s.T + it.t, floorT)};
-                    if (c.W + preMinW[i] > I.B1 || c.T + preMinT[i] > I.B2) continue;
-                    bool cut = false;
-                    for (size_t m = 0; m < M && !cut; ++m) {
-                        const double a = (double)c.Z * Sd[m], b = L1d[m] * (double)c.W, d = L2d[m] * (double)c.T;
-                        const double lhs_d = a + b + d + preRCd[m][i], rhs_d = (double)cutoff * Sd[m];
-                        const double tol = 1e-9 * (std::fabs(a) + std::fabs(b) + std::fabs(d) + std::fabs(preRCd[m][i]) + std::fabs(rhs_d));
-                        if (lhs_d > rhs_d + tol) { cut = true; break; }
-                        if (lhs_d < rhs_d - tol) continue;
-                        const i128 lhs = (i128)c.Z * mult[m].S + mult[m].L1 * (i128)c.W + mult[m].L2 * (i128)c.T + preRC[m][i];
-                        cut = lhs > (i128)cutoff * mult[m].S;
-                    }
-                    if (cut) continue;
-                    cand.push_back(c);
-                }
+    // Step 1, the optimal value.  The order of the levels is free here, and it decides how long the lists get: blocks
+    // whose best configuration under the multipliers leads the second best by a wide margin come last (they are
+    // processed first and hardly branch, since any other choice fails the bound at once), the undecided blocks come
+    // first, where the levels still to come are few and their bound is sharp.
+    std::vector<uint32_t> perm(N);
+    {
+        const double m1 = l1 < 1e29 ? l1 : 0.0, m2 = l2 < 1e29 ? l2 : 0.0;
+        std::vector<double> lead(N);
+        for (uint32_t i = 0; i < N; ++i) {
+            double lo = std::numeric_limits<double>::infinity(), lo2 = lo;
+            for (const Item& it : I.items[i]) {
+                const double rc = (double)it.phi + m1 * (double)it.w + m2 * (double)it.t;
+                if (rc < lo) { lo2 = lo; lo = rc; } else if (rc < lo2) lo2 = rc;
             }
-            if (cand.empty()) return kRunEmpty;
-            // keep what nothing undercuts: sweep by (W, T, Z) with a staircase over T of the least Z seen
-            const size_t n = cand.size();
-            std::vector<State>& out = lists[i];
-            out.clear();
-            order.resize(n);
-            for (size_t j = 0; j < n; ++j) order[j] = (uint32_t)j;
-            std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-                const State &x = cand[a], &y = cand[b];
-                if (x.W != y.W) return x.W < y.W;
-                if (x.T != y.T) return x.T < y.T;
-                return x.Z < y.Z;
-            });
-            stair.clear();
-            for (uint32_t j : order) {
-                const State& s = cand[j];
-                // first entry with T > s.T; the one before it holds the least Z among swept states with time <= s.T
-                auto it = std::upper_bound(stair.begin(), stair.end(), s.T,
-                                           [](int64_t t, const std::pair<int64_t, int64_t>& e) { return t < e.first; });
-                if (it != stair.begin() && std::prev(it)->second <= s.Z) continue;      // undercut (or equalled)
-                if (it != stair.begin() && std::prev(it)->first == s.T) { --it; it->second = s.Z; }
-                else it = stair.insert(it, std::make_pair(s.T, s.Z));
-                auto nx = std::next(it), e = nx;
-                while (e != stair.end() && e->second >= s.Z) ++e;                        // entries to the right that are no better
-                stair.erase(nx, e);
-                out.push_back(s);
-            }
-            total += out.size();
-            if (total > limit) return kRunLimit;
+            lead[i] = lo2 - lo;                        // infinite for a block with one configuration
+            perm[i] = i;
         }
-        return kRunOk;
-    };
-    auto best_final = [&]() {                          // least Z among the states of level 0 (all of them are feasible)
-        int64_t z = kInf64;
-        for (const State& s : lists[0]) z = std::min(z, s.Z);
-        return z;
-    };
+        std::stable_sort(perm.begin(), perm.end(), [&](uint32_t a, uint32_t b) { return lead[a] < lead[b]; });
+    }
+    Instance J;
+    J.N = N; J.B1 = I.B1; J.B2 = I.B2; J.items.resize(N);
+    for (uint32_t j = 0; j < N; ++j) J.items[j] = I.items[perm[j]];
+    Levels LJ(J, mult);
 
     // Cutoffs rise from the smallest lattice value that the bound of the whole instance allows towards the
     // incumbent: a run that ends empty proves that the optimum lies above its cutoff, the first run that reaches
@@ -347,7 +453,7 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
     // surviving states grows steeply with that width), and the empty runs before it are cheap.
     int64_t low = ub;
     {
-        const i128 room = (i128)ub * mult[0].S - preRC[0][N];                  // S (ub - bound of the whole instance)
+        const i128 room = (i128)ub * mult[0].S - LJ.preRC[0][N];               // S (ub - bound of the whole instance)
         if (room > 0) low = ub - (int64_t)(room / (mult[0].S * (i128)g)) * g;
     }
     int rc;
@@ -355,7 +461,7 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
         const int64_t span = (ub - low) / g;               // lattice steps from low to the incumbent
         int64_t at = 0, step = std::max<int64_t>(1, span >> 20);
         for (;;) {
-            rc = run(low + at * g);
+            rc = LJ.run(low + at * g, limit);
             if (rc != kRunEmpty || at >= span) break;
             at = std::min(span, at + step);
             step = std::max(step + 1, step + step / 2);
@@ -363,17 +469,33 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
     }
     if (rc == kRunLimit) return BAOC_ERR_LIMIT;
     if (rc == kRunEmpty) return BAOC_ERR_INFEASIBLE;
+    int64_t z_star = kInf64;                           // least Z among the states of level 0 (all of them are feasible)
+    for (const State& s : LJ.lists[0]) z_star = std::min(z_star, s.Z);
 
-    // The canonical optimum, block by block: the smallest configuration index for which some kept suffix
-    // state still completes the prefix to the optimal value within both budgets.
-    const int64_t z_star = best_final();
+    // Step 2, the configurations that occur in optimal assignments at all (usually one per block, or a few).
+    std::vector<std::vector<uint8_t>> mark;
+    rc = LJ.viable(z_star, limit, mark);
+    if (rc != kRunOk) return BAOC_ERR_LIMIT;           // kRunEmpty cannot happen: an optimal assignment exists
+    Instance R;
+    R.N = N; R.B1 = I.B1; R.B2 = I.B2; R.items.resize(N);
+    for (uint32_t j = 0; j < N; ++j)
+        for (size_t k = 0; k < J.items[j].size(); ++k)
+            if (mark[j][k]) R.items[perm[j]].push_back(J.items[j][k]);          // ascending configuration index, as in I
+    LJ.lists.clear(); LJ.lists.shrink_to_fit();
+
+    // Step 3, the canonical optimum: the recursion once more, in index order, over those configurations only and
+    // with the optimal value as cutoff; then block by block the smallest configuration index for which some kept
+    // state of the next list still completes the prefix to the optimal value within both budgets.
+    Levels LR(R, mult);
+    rc = LR.run(z_star, limit);
+    if (rc != kRunOk) return BAOC_ERR_LIMIT;
     answer.assign(N, 0);
     int64_t Zp = 0, Wp = 0, Tp = 0;
     for (uint32_t i = 0; i < N; ++i) {
         bool placed = false;
-        for (const Item& it : I.items[i]) {            // ascending configuration index
+        for (const Item& it : R.items[i]) {
             const int64_t z = Zp + it.phi, w = Wp + it.w, t = Tp + it.t;
-            for (const State& s : lists[i + 1])
+            for (const State& s : LR.lists[i + 1])
                 if (z + s.Z <= z_star && w + s.W <= I.B1 && t + s.T <= I.B2) { placed = true; break; }
             if (placed) { answer[i] = it.cfg; Zp = z; Wp = w; Tp = t; break; }
         }
