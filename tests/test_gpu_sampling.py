@@ -4,9 +4,9 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle.runner import assert_stats_close, oracle_params, to_host_bits
+from oracle.runner import OracleRunner, assert_risk_close, assert_stats_close, oracle_params, to_host_bits
 from synth import workloads as W
-from test_gpu_parity import env, ragged_workload  # noqa: F401
+from test_gpu_parity import check_allocation, env, ragged_workload  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -103,6 +103,47 @@ def test_full_size_sampling_of_the_7b_layout(env):  # noqa: F811
         assert np.array_equal(smp.indices(i).cpu().numpy(), want) and tuple(smp.compact_blocks[i][2:]) == shape
         o, n = smp.compact_blocks[i][0], smp.compact_blocks[i][1]
         assert torch.equal(compact[o:o + n], buf[torch.from_numpy(want).cuda()])
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_full_size_sampled_window_of_the_7b_layout(env, seed):  # noqa: F811
+    """The front end of Sec. 3.1 at its real shape and the paper's ratio: s = 0.1 % of the 7B-shaped layout (6.7 M of
+    6.7 G coordinates), gradient streams of seeds 1 to 3.  Every gathered value is its sampled coordinate's; the
+    profiler on the compact layout agrees with the oracle on every block (F of Eq. 7 on the sampled sub-matrices, C of
+    Eq. 6 on the sampled parameters); the allocation for the full-size costs on that risk table is the oracle's."""
+    from collections import namedtuple
+    torch, binding, device = env["torch"], env["binding"], env["device"]
+    w = W.make("llama7b", seed=seed)
+    smp = binding.Sampler(w.blocks, 0.001, 5)
+    CB = namedtuple("CB", "offset numel rows cols")
+    cblocks = [CB(*b) for b in smp.compact_blocks]
+    assert sum(b.rows > 0 for b in cblocks) == sum(b.rows > 0 for b in w.blocks)          # every matrix block keeps a matrix form
+    params = binding.default_profile_params(grad_dtype=1)
+    prof = binding.Profiler(smp.compact_blocks, params)
+    orc = OracleRunner(cblocks, None, **oracle_params(params))
+    idx = [smp.indices(i) for i in range(len(w.blocks))]
+    buf, compact = device.new_buffer(w), None
+    for t in range(1, 5):
+        device.fill(w, buf, seed, t)
+        compact = smp.gather(buf, compact)
+        for i, b in enumerate(cblocks):
+            assert torch.equal(compact[b.offset:b.offset + b.numel], buf[idx[i]]), f"gathered values of block {i}, step {t}"
+        prof.step(compact)
+        orc.step_from_device(compact)
+    del buf
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(99 + seed)
+    theta = torch.empty(w.buffer_numel, dtype=torch.bfloat16, device="cuda:0")
+    for o in range(0, w.buffer_numel, 1 << 28):                                          # in pieces: no 27 GB fp32 temporary
+        n = min(1 << 28, w.buffer_numel - o)
+        theta[o:o + n] = (0.02 * torch.randn(n, device="cuda:0", generator=gen)).to(torch.bfloat16)
+    ctheta = smp.gather(theta)
+    stats, risk = prof.finalize(w.configs, theta=ctheta)
+    ostats, orisk = orc.finalize(w.configs, shapes=[(b.rows, b.cols) for b in cblocks], theta=ctheta)
+    for i, b in enumerate(cblocks):
+        assert_stats_close(stats[i], ostats[i], f"sampled block {i} ({w.blocks[i].name}, {b.numel} of {w.blocks[i].numel})")
+        assert_risk_close(risk[i], orisk[i], f"sampled block {i}")
+    assert sum(st.F > 0 for st in stats) * 2 >= sum(b.rows > 1 and b.cols > 1 for b in cblocks) > 200        # F exists under sampling
+    check_allocation(env, w, risk)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
