@@ -226,6 +226,10 @@ void keep_undercut_free(std::vector<State>& cand, std::vector<State>& out, std::
 }
 
 enum { kRunOk = 0, kRunEmpty = 1, kRunLimit = 3 };
+// The forward pass of Levels::viable is exact while it is cheap: after this many extended states, fronts are cut
+// down to kFrontCap states per level (still marking every configuration it must, and then some more).
+constexpr uint64_t kExactWork = 16'000'000ull;
+constexpr size_t kFrontCap = 256;
 
 // The list recursion over one ordering of the blocks ("levels"): lists[i] holds states of the levels i..N-1.
 struct Levels {
@@ -312,26 +316,58 @@ struct Levels {
         return kRunOk;
     }
 
-    // After a run that reached level 0 with a cutoff >= z: which configurations occur in some feasible assignment
-    // of value <= z.  Forward over the levels: front holds states of the levels before i (true sums); a state
-    // extended by a configuration is kept when some state of lists[i+1] completes it within z and both budgets,
-    // and the configuration is marked.  Exact in both directions: a kept pair is an assignment, and the part of
-    // any assignment of value <= z before and after level i is undercut by a state of front and of lists[i+1].
-    int viable(int64_t z, uint64_t limit, std::vector<std::vector<uint8_t>>& mark)
+    // A long front is replaced by fewer, more optimistic states: runs of neighbours in (Z, W) order collapse to
+    // their least Z, W and T (within one value of Z the times fall as the memory rises, so a run is a short piece
+    // of that staircase and its stand-in the corner below it).  Whatever completes a member completes its
+    // stand-in.  Runs stop at a change of Z unless the values of Z alone outnumber the cap.
+    void thin(std::vector<State>& front, std::vector<State>& tmp)
+    {
+        std::sort(front.begin(), front.end(), [](const State& a, const State& b) { return a.Z != b.Z ? a.Z < b.Z : a.W < b.W; });
+        const size_t n = front.size(), len = (n + kFrontCap - 1) / kFrontCap;
+        size_t values = 1;
+        for (size_t a = 1; a < n; ++a) values += front[a].Z != front[a - 1].Z;
+        const bool across = values > kFrontCap;
+        tmp.clear();
+        for (size_t a = 0; a < n;) {
+            State m = front[a];
+            size_t b = a + 1;
+            for (; b < std::min(n, a + len) && (across || front[b].Z == front[a].Z); ++b) {
+                m.Z = std::min(m.Z, front[b].Z); m.W = std::min(m.W, front[b].W); m.T = std::min(m.T, front[b].T);
+            }
+            tmp.push_back(m);
+            a = b;
+        }
+        keep_undercut_free(tmp, front, order, stair);
+    }
+
+    // After a run that reached level 0 with a cutoff >= z: marks every configuration that occurs in some feasible
+    // assignment of value <= z (and, once the fronts are thinned, possibly some that do not).  Forward over the
+    // levels: front holds states of the levels before i; a state extended by a configuration is kept
+    // when some state of lists[i+1] completes it within z and both budgets, and the configuration is marked.
+    // Nothing is missed: the parts of any assignment of value <= z before and after level i are undercut by a state
+    // of front and of lists[i+1].  Until the fronts are thinned the marks are exact: a kept pair is an
+    // assignment.
+    int viable(int64_t z, std::vector<std::vector<uint8_t>>& mark)
     {
         struct Ext { State s; uint32_t k; };
         std::vector<Ext> ext;
         std::vector<State> front(1, State{0, 0, 0}), kept;
-        uint64_t total = 1;
+        uint64_t work = 0;
         mark.assign(N, std::vector<uint8_t>());
         for (uint32_t i = 0; i < N; ++i) {
             mark[i].assign(I.items[i].size(), 0);
+            // The clamp of run(), mirrored: a row that the levels after i cannot push over its budget any more does
+            // not tell states of the levels 0..i apart (the second term keeps a clamped state within what those
+            // levels can use at all, so that it still fits the clamped states of lists[i+1]).
+            const int64_t floorW = std::min(I.B1 - (preMaxW[N] - preMaxW[i + 1]), preMaxW[i + 1]);
+            const int64_t floorT = std::min(I.B2 - (preMaxT[N] - preMaxT[i + 1]), preMaxT[i + 1]);
             ext.clear();
             for (const State& p : front)
                 for (uint32_t k = 0; k < I.items[i].size(); ++k) {
                     const Item& it = I.items[i][k];
-                    ext.push_back(Ext{State{p.Z + it.phi, p.W + it.w, p.T + it.t}, k});
+                    ext.push_back(Ext{State{p.Z + it.phi, std::max(p.W + it.w, floorW), std::max(p.T + it.t, floorT)}, k});
                 }
+            work += ext.size();
             // most room in the memory row last: the states of lists[i+1] come in ascending W and enter the staircase as they fit
             std::sort(ext.begin(), ext.end(), [](const Ext& a, const Ext& b) { return a.s.W > b.s.W; });
             stair.clear();
@@ -345,8 +381,7 @@ struct Levels {
             }
             if (kept.empty()) return kRunEmpty;
             keep_undercut_free(kept, front, order, stair);
-            total += front.size();
-            if (total > limit) return kRunLimit;
+            if (work > kExactWork && front.size() > kFrontCap) thin(front, kept);
         }
         return kRunOk;
     }
@@ -474,8 +509,8 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
 
     // Step 2, the configurations that occur in optimal assignments at all (usually one per block, or a few).
     std::vector<std::vector<uint8_t>> mark;
-    rc = LJ.viable(z_star, limit, mark);
-    if (rc != kRunOk) return BAOC_ERR_LIMIT;           // kRunEmpty cannot happen: an optimal assignment exists
+    rc = LJ.viable(z_star, mark);
+    if (rc != kRunOk) return BAOC_ERR_LIMIT;           // cannot happen: an optimal assignment exists
     Instance R;
     R.N = N; R.B1 = I.B1; R.B2 = I.B2; R.items.resize(N);
     for (uint32_t j = 0; j < N; ++j)
