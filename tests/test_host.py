@@ -315,6 +315,29 @@ def test_allocate_both_rows_binding(name, K, kind, ratio, capf, tmode, excl):
                   options=dict(mip_rel_gap=0.0, time_limit=60))
         if ip.success and ip.status == 0:
             assert obj <= ip.fun + 1e-6
+        # and no lexicographically smaller assignment is as good, as far as a library solver can tell: for a few
+        # (block i, configuration c < x_i), the best assignment that keeps x_0..x_{i-1} and takes c at block i must
+        # cost more in the integer image (checked there exactly) than the answer does
+        phi = np.rint(np.clip(risk, -1e6, 1e6) * 1e9).astype(np.int64)
+        tau = np.rint(tc * 1e6).astype(np.int64)
+        B2, rows = int(round(cap * 1e6)), np.arange(N)
+        Z = int(phi[rows, x].sum())
+        probes = [(i, c) for i in range(N) for c in range(int(x[i])) if fb is None or not fb[i, c]]
+        near = sorted(range(len(probes)), key=lambda j: abs(int(phi[probes[j]]) - int(phi[probes[j][0], x[probes[j][0]]])))[:5]
+        for j in list(rng.choice(len(probes), min(4, len(probes)), replace=False)) + near:   # some anywhere, some near-ties
+            i, c = probes[j]
+            lo, hi = np.zeros((N, K)), ub.reshape(N, K).copy()
+            hi[:i] = 0.0
+            hi[rows[:i], x[:i]] = 1.0
+            hi[i] = 0.0
+            hi[i, c] = 1.0
+            ip = milp(risk.reshape(-1), constraints=cons, integrality=np.ones(N * K), bounds=Bounds(lo.reshape(-1), hi.reshape(-1)),
+                      options=dict(mip_rel_gap=0.0, time_limit=20))
+            if not (ip.success and ip.status == 0):
+                continue                                                          # infeasible, or no verdict in time
+            y = ip.x.reshape(N, K).argmax(1)
+            if mem[rows, y].sum() <= bm and tau[rows, y].sum() <= B2:
+                assert int(phi[rows, y].sum()) > Z, (i, c, "a lexicographically smaller assignment costs no more")
 
 
 def test_bench_refuses_more_than_one_gpu():
