@@ -293,6 +293,13 @@ int baoc_partition(const uint64_t* unit_numel, const double* z, uint32_t n_units
  * this thread's later calls; 0 = default (32 M).  Beyond it the call returns BAOC_ERR_LIMIT. */
 void baoc_allocate_set_node_limit(uint64_t max_nodes);
 
+/* Work the solver spends on finding exactly which configurations occur in optimal assignments (max_states:
+ * states extended by its forward pass), for this thread's later calls; 0 = default (16 M, about a second).
+ * Beyond it the pass goes on with at most front_cap coarser, optimistic states per level (0 = default, 256):
+ * the answer is the same, only the last recursion of the call has more configurations to carry.  Tuning
+ * knobs (Eq. 2 does not know them); max_states = 1 switches the exact phase off. */
+void baoc_allocate_set_exact_work(uint64_t max_states, uint32_t front_cap);
+
 const char* baoc_status_string(int status);
 
 #ifdef __cplusplus

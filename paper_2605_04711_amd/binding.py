@@ -94,6 +94,8 @@ def load_library():
     L.baoc_partition.argtypes = [vp, vp, u32, u32, vp, f64, vp, C.POINTER(u32), C.POINTER(f64)]
     L.baoc_allocate_set_node_limit.argtypes = [u64]
     L.baoc_allocate_set_node_limit.restype = None
+    L.baoc_allocate_set_exact_work.argtypes = [u64, u32]
+    L.baoc_allocate_set_exact_work.restype = None
     L.baoc_status_string.argtypes = [C.c_int]
     L.baoc_status_string.restype = C.c_char_p
     _lib = L

@@ -52,7 +52,8 @@ struct Instance {
     int64_t B1 = 0, B2 = 0;
 };
 
-thread_local uint64_t g_node_limit = 0;
+thread_local uint64_t g_node_limit = 0, g_exact_work = 0;
+thread_local uint32_t g_front_cap = 0;
 constexpr uint64_t kDefaultNodeLimit = 32'000'000ull;      // states kept over all levels (24 bytes each)
 
 inline double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
@@ -226,10 +227,10 @@ void keep_undercut_free(std::vector<State>& cand, std::vector<State>& out, std::
 }
 
 enum { kRunOk = 0, kRunEmpty = 1, kRunLimit = 3 };
-// The forward pass of Levels::viable is exact while it is cheap: after this many extended states, fronts are cut
-// down to kFrontCap states per level (still marking every configuration it must, and then some more).
-constexpr uint64_t kExactWork = 16'000'000ull;
-constexpr size_t kFrontCap = 256;
+// The forward pass of Levels::viable is exact while it is cheap: after this many extended states (by default), fronts are cut
+// down to a few hundred states per level (still marking every configuration it must, and then some more).
+constexpr uint64_t kDefaultExactWork = 16'000'000ull;
+constexpr size_t kDefaultFrontCap = 256;
 
 // The list recursion over one ordering of the blocks ("levels"): lists[i] holds states of the levels i..N-1.
 struct Levels {
@@ -320,13 +321,13 @@ struct Levels {
     // their least Z, W and T (within one value of Z the times fall as the memory rises, so a run is a short piece
     // of that staircase and its stand-in the corner below it).  Whatever completes a member completes its
     // stand-in.  Runs stop at a change of Z unless the values of Z alone outnumber the cap.
-    void thin(std::vector<State>& front, std::vector<State>& tmp)
+    void thin(std::vector<State>& front, std::vector<State>& tmp, size_t cap)
     {
         std::sort(front.begin(), front.end(), [](const State& a, const State& b) { return a.Z != b.Z ? a.Z < b.Z : a.W < b.W; });
-        const size_t n = front.size(), len = (n + kFrontCap - 1) / kFrontCap;
+        const size_t n = front.size(), len = (n + cap - 1) / cap;
         size_t values = 1;
         for (size_t a = 1; a < n; ++a) values += front[a].Z != front[a - 1].Z;
-        const bool across = values > kFrontCap;
+        const bool across = values > cap;
         tmp.clear();
         for (size_t a = 0; a < n;) {
             State m = front[a];
@@ -353,6 +354,8 @@ struct Levels {
         std::vector<Ext> ext;
         std::vector<State> front(1, State{0, 0, 0}), kept;
         uint64_t work = 0;
+        const uint64_t exact_work = g_exact_work ? g_exact_work : kDefaultExactWork;
+        const size_t front_cap = g_front_cap ? g_front_cap : kDefaultFrontCap;
         mark.assign(N, std::vector<uint8_t>());
         for (uint32_t i = 0; i < N; ++i) {
             mark[i].assign(I.items[i].size(), 0);
@@ -381,7 +384,7 @@ struct Levels {
             }
             if (kept.empty()) return kRunEmpty;
             keep_undercut_free(kept, front, order, stair);
-            if (work > kExactWork && front.size() > kFrontCap) thin(front, kept);
+            if (work > exact_work && front.size() > front_cap) thin(front, kept, front_cap);
         }
         return kRunOk;
     }
@@ -542,6 +545,7 @@ int solve(const Instance& I, std::vector<uint32_t>& answer)
 }  // namespace
 
 extern "C" void baoc_allocate_set_node_limit(uint64_t max_nodes) { g_node_limit = max_nodes; }
+extern "C" void baoc_allocate_set_exact_work(uint64_t max_states, uint32_t front_cap) { g_exact_work = max_states; g_front_cap = front_cap; }
 
 static int allocate(const double* risk, const int64_t* mem, const double* time_cost,
                     uint32_t N, uint32_t K, int64_t mem_budget, double time_budget_sum,

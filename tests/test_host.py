@@ -272,6 +272,30 @@ def test_allocate_full_size_grid_is_fast_and_canonical(name, K):
         assert list(x) == list(ref[1]) and (obj, m, t) == tuple(ref[2:]), (name, K, kind)
 
 
+@pytest.mark.parametrize("name,K", [("unet", 6), ("llama7b", 21), ("resnet50", 21)])
+def test_allocate_answer_does_not_depend_on_the_exact_work_budget(name, K):
+    """With the exact phase of the forward pass switched off and its fronts thinned to at most 4 optimistic stand-ins
+    per level from the first level on, more configurations reach the last recursion, and the answer is still the
+    oracle's, on continuous, tie-heavy and budget-binding tables."""
+    import alloc_families as F
+    w, cfgs, mem, tc, bm, cap = F.costs(name, K)
+    N = len(w.blocks)
+    lib = B.load_library()
+    for j, kind in enumerate(F.KINDS):
+        if kind not in ("continuous", "integer", "round1", "saturated", "integer+", "round3+"):
+            continue
+        rng = np.random.default_rng([N, K, j])
+        risk = F.family(rng, kind, N, cfgs, mem)
+        ref = oracle.allocate_bnb(risk, mem, tc, bm, cap, node_limit=400_000_000)
+        assert ref[0] == 0, (name, K, kind, "oracle did not finish")
+        lib.baoc_allocate_set_exact_work(1, 4)
+        try:
+            x, obj, m, t = B.allocate(risk, mem, tc, bm, cap)
+        finally:
+            lib.baoc_allocate_set_exact_work(0, 0)
+        assert list(x) == list(ref[1]) and (obj, m, t) == tuple(ref[2:]), (name, K, kind)
+
+
 # Both rows binding, generic (measured-like) time costs, exclusions: harder for both solvers.  Cells where the
 # oracle's search exceeds its node limit are parity unpinned for the choice vector; there the answer must still
 # be feasible and no worse than what a library MILP solver finds.
@@ -305,6 +329,12 @@ def test_allocate_both_rows_binding(name, K, kind, ratio, capf, tmode, excl):
     ref = oracle.allocate_bnb(risk, mem, tc, bm, cap, fb, node_limit=5_000_000)
     if ref[0] == 0:
         assert list(x) == list(ref[1]) and (obj, m, t) == tuple(ref[2:])
+        B.load_library().baoc_allocate_set_exact_work(1, 4)                       # forward pass thinned from the first level on
+        try:
+            x2, *rest = B.allocate(risk, mem, tc, bm, cap, fb)
+        finally:
+            B.load_library().baoc_allocate_set_exact_work(0, 0)
+        assert list(x2) == list(ref[1]) and tuple(rest) == tuple(ref[2:])
     else:
         assert ref[0] == oracle.ORC_TOO_BIG                                       # parity unpinned for this cell
         ub = np.ones(N * K) if fb is None else 1.0 - fb.reshape(-1)
