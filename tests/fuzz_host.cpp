@@ -30,6 +30,7 @@ int main()
         const double bt = tlo + U(-0.05, 1.0) * (thi - tlo);
         std::vector<uint32_t> choice(N); double obj; int64_t om; double ot;
         baoc_allocate_set_node_limit(trial % 3 == 0 ? 20000 : 0);
+        if (trial % 4 == 1) baoc_allocate_set_exact_work(1, 1 + trial % 7); else baoc_allocate_set_exact_work(0, 0);   // thinned forward pass
         const int rc = baoc_allocate(risk.data(), mem.data(), tc.data(), N, K, bm, bt, trial % 2 ? fb.data() : nullptr, choice.data(), &obj, &om, &ot);
         if (rc == BAOC_OK) { ++ok; for (uint32_t i = 0; i < N; ++i) if (choice[i] >= K) { printf("bad choice\n"); return 1; } if (om > bm) { printf("budget violated\n"); return 1; } }
         else if (rc == BAOC_ERR_INFEASIBLE) ++inf; else if (rc == BAOC_ERR_LIMIT) ++lim; else ++inv;
