@@ -47,6 +47,17 @@ def test_fullsize_unet_other_seeds(env, seed):  # noqa: F811
     check_allocation(env, w, risk)
 
 
+@pytest.mark.parametrize("name,seed", [("gpt_1p3b", 2), ("llama7b", 3)])
+def test_fullsize_language_layouts_other_seeds(env, name, seed):  # noqa: F811
+    """The 1.3B- and 7B-shaped layouts on another seed each (layout statistics and stream), short windows."""
+    w = W.make(name, seed=seed)
+    only = sample_blocks(w, seed=11 + seed, cap=40_000_000)
+    torch = env["torch"]
+    prof, stats, risk, ostats, orisk = run_both(env, w, 3, only=only, check_state=True, seed=seed,
+                                                theta_dtype=torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32)
+    check_allocation(env, w, risk)
+
+
 def test_blocks_beyond_2_to_the_31_coordinates(env):  # noqa: F811
     """One vector block and one matrix block of more than 2^31 coordinates each, fed a constant gradient: the
     intensive statistics equal those of a small oracle block on the same gradient and the extensive ones scale
