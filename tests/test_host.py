@@ -364,7 +364,7 @@ def test_allocate_both_rows_binding(name, K, kind, ratio, capf, tmode, excl):
             ip = milp(risk.reshape(-1), constraints=cons, integrality=np.ones(N * K), bounds=Bounds(lo.reshape(-1), hi.reshape(-1)),
                       options=dict(mip_rel_gap=0.0, time_limit=20))
             if not (ip.success and ip.status == 0):
-                continue                                                          # infeasible, or no verdict in time
+                continue                                                          # infeasible, or no answer in time
             y = ip.x.reshape(N, K).argmax(1)
             if mem[rows, y].sum() <= bm and tau[rows, y].sum() <= B2:
                 assert int(phi[rows, y].sum()) > Z, (i, c, "a lexicographically smaller assignment costs no more")
